@@ -1,0 +1,332 @@
+/*
+ * CPU oracle for the batch renderer  --  TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may call
+ * this.  It shares no code with the GPU library and is never a fallback for it.
+ *
+ * What it computes (paper Sec. 3, Sec. 3.2: one request per environment, N frames
+ * out; K scenes shared by reference): for every environment b and every pixel
+ * centre of its H x W frame, the nearest triangle of scene s_b as seen through
+ * view_proj[b].  The paper delegates rasterisation to the graphics API and states
+ * no rule, so the rule below is this build's numeric contract:
+ *
+ *   N0  binary32, round-to-nearest-even, no contraction, fmaf exactly where written.
+ *   N1  clip = M (x,y,z,1): c_r = fma(M[r][2],z, fma(M[r][1],y, fma(M[r][0],x, M[r][3]))).
+ *   N2  six planes d0=w+x d1=w-x d2=w+y d3=w-y d4=z d5=w-z, inside iff d >= 0.
+ *       Any non-finite clip coordinate drops the triangle; all three vertices outside
+ *       one plane drops it; all inside every plane leaves it whole; otherwise N3.
+ *   N3  Sutherland-Hodgman, planes in order near, far, left, right, top, bottom
+ *       (4,5,0,1,2,3), skipping planes no original vertex is outside of.  A crossing
+ *       is always interpolated from the inside vertex a to the outside vertex b:
+ *       t = d(a) / (d(a) - d(b)), p = fma(t, b - a, a) per attribute.
+ *   N4  w > 0 required; iw = 1/w; xn = x*iw; yn = y*iw;
+ *       X = lrint(fma(xn, 128 W, 128 W)), Y likewise with H: 1/256-pixel units,
+ *       origin at the top-left corner of pixel (0,0), y down.  A vertex whose
+ *       un-rounded coordinate leaves [-64, 256 W + 64] (or is NaN) drops the triangle.
+ *   N5  fan (q0, qi, qi+1); A2 = (X1-X0)(Y2-Y0) - (X2-X0)(Y1-Y0); A2 = 0 skipped;
+ *       A2 < 0: swap vertices 1 and 2 (two-sided).  Edge i is opposite vertex i,
+ *       E(p) = dx (py - Yj) - dy (px - Xj) for edge j -> k.
+ *   N6  covered iff every E_i > 0, or E_i = 0 on a top-left edge
+ *       (dy < 0, or dy = 0 and dx > 0), at pixel centre (256 i + 128, 256 j + 128).
+ *   N7  depth = (float)A2 / fma(e2,iw2, fma(e1,iw1, e0*iw0)), e_i = (float)E_i:
+ *       perspective-correct clip w.  key = depth bits << 32 | original triangle id;
+ *       the pixel keeps the minimum key.
+ *   N8  uncovered pixel: depth = background, id = 0xFFFFFFFF, rgb = 0.
+ *   N9  colour: cn = fma(e2*iw2,c2, fma(e1*iw1,c1, (e0*iw0)*c0)); out = clamp(lrint(cn/num)).
+ *
+ * Everything after N4 is exact integer arithmetic in int64.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define MAXPOLY 16
+
+typedef struct {
+    float c[4];   /* clip x, y, z, w */
+    float col[3]; /* r, g, b as floats */
+} overt;
+
+typedef struct {
+    int H, W;
+    uint64_t *key;   /* [H*W] */
+    uint32_t *cover; /* [H*W] or NULL: number of covering sub-triangles */
+    uint8_t *rgb;    /* [H*W*3] or NULL */
+} oframe;
+
+static float plane_dist(const overt *v, int k)
+{
+    switch (k) {
+    case 0: return v->c[3] + v->c[0];
+    case 1: return v->c[3] - v->c[0];
+    case 2: return v->c[3] + v->c[1];
+    case 3: return v->c[3] - v->c[1];
+    case 4: return v->c[2];
+    default: return v->c[3] - v->c[2];
+    }
+}
+
+/* N1 */
+static void transform(const float *M, const float *p, overt *o)
+{
+    for (int r = 0; r < 4; ++r)
+        o->c[r] = fmaf(M[r * 4 + 2], p[2], fmaf(M[r * 4 + 1], p[1], fmaf(M[r * 4 + 0], p[0], M[r * 4 + 3])));
+}
+
+/* N3: crossing point, always from the inside vertex a towards the outside vertex b */
+static void intersect(const overt *a, const overt *b, int k, overt *o)
+{
+    float da = plane_dist(a, k), db = plane_dist(b, k);
+    float t = da / (da - db);
+    for (int i = 0; i < 4; ++i) o->c[i] = fmaf(t, b->c[i] - a->c[i], a->c[i]);
+    for (int i = 0; i < 3; ++i) o->col[i] = fmaf(t, b->col[i] - a->col[i], a->col[i]);
+}
+
+/* N2 + N3.  Returns the polygon's vertex count (0 = dropped). */
+static int clip_triangle(const overt tri[3], overt *poly)
+{
+    int out_any[6] = {0, 0, 0, 0, 0, 0};
+    for (int v = 0; v < 3; ++v)
+        for (int i = 0; i < 4; ++i)
+            if (!isfinite(tri[v].c[i])) return 0;
+    for (int k = 0; k < 6; ++k) {
+        int nout = 0;
+        for (int v = 0; v < 3; ++v)
+            if (!(plane_dist(&tri[v], k) >= 0.0f)) ++nout;
+        if (nout == 3) return 0;
+        out_any[k] = nout > 0;
+    }
+    overt bufa[MAXPOLY], bufb[MAXPOLY];
+    overt *cur = bufa, *nxt = bufb;
+    int n = 3;
+    memcpy(cur, tri, 3 * sizeof(overt));
+    static const int order[6] = {4, 5, 0, 1, 2, 3};
+    for (int oi = 0; oi < 6; ++oi) {
+        int k = order[oi];
+        if (!out_any[k]) continue;
+        int m = 0;
+        for (int i = 0; i < n; ++i) {
+            const overt *c = &cur[i];
+            const overt *p = &cur[(i + n - 1) % n];
+            int cin = plane_dist(c, k) >= 0.0f;
+            int pin = plane_dist(p, k) >= 0.0f;
+            if (cin) {
+                if (!pin) intersect(c, p, k, &nxt[m++]);
+                nxt[m++] = *c;
+            } else if (pin) {
+                intersect(p, c, k, &nxt[m++]);
+            }
+        }
+        n = m;
+        overt *t = cur; cur = nxt; nxt = t;
+        if (n < 3) return 0;
+    }
+    memcpy(poly, cur, (size_t)n * sizeof(overt));
+    return n;
+}
+
+static int64_t floor_div(int64_t a, int64_t b) /* b > 0 */
+{
+    int64_t q = a / b;
+    if ((a % b) != 0 && a < 0) --q;
+    return q;
+}
+
+/* N5-N9 on one fan triangle with snapped vertices */
+static void raster_subtri(oframe *f, const int64_t Xi[3], const int64_t Yi[3], const float iwi[3],
+                          float coli[3][3], uint32_t id)
+{
+    int64_t X[3] = {Xi[0], Xi[1], Xi[2]}, Y[3] = {Yi[0], Yi[1], Yi[2]};
+    float iw[3] = {iwi[0], iwi[1], iwi[2]};
+    float col[3][3];
+    memcpy(col, coli, sizeof(col));
+    int64_t A2 = (X[1] - X[0]) * (Y[2] - Y[0]) - (X[2] - X[0]) * (Y[1] - Y[0]);
+    if (A2 == 0) return;
+    if (A2 < 0) {
+        int64_t t;
+        float ft;
+        t = X[1]; X[1] = X[2]; X[2] = t;
+        t = Y[1]; Y[1] = Y[2]; Y[2] = t;
+        ft = iw[1]; iw[1] = iw[2]; iw[2] = ft;
+        for (int c = 0; c < 3; ++c) { ft = col[1][c]; col[1][c] = col[2][c]; col[2][c] = ft; }
+        A2 = -A2;
+    }
+    int64_t minX = X[0], maxX = X[0], minY = Y[0], maxY = Y[0];
+    for (int v = 1; v < 3; ++v) {
+        if (X[v] < minX) minX = X[v];
+        if (X[v] > maxX) maxX = X[v];
+        if (Y[v] < minY) minY = Y[v];
+        if (Y[v] > maxY) maxY = Y[v];
+    }
+    /* pixel centres 256 i + 128 inside the closed bounding box, clamped to the frame */
+    int64_t i0 = -floor_div(-(minX - 128), 256), i1 = floor_div(maxX - 128, 256);
+    int64_t j0 = -floor_div(-(minY - 128), 256), j1 = floor_div(maxY - 128, 256);
+    if (i0 < 0) i0 = 0;
+    if (j0 < 0) j0 = 0;
+    if (i1 > f->W - 1) i1 = f->W - 1;
+    if (j1 > f->H - 1) j1 = f->H - 1;
+    for (int64_t j = j0; j <= j1; ++j) {
+        for (int64_t i = i0; i <= i1; ++i) {
+            int64_t px = 256 * i + 128, py = 256 * j + 128;
+            int64_t E[3];
+            int in = 1;
+            for (int e = 0; e < 3; ++e) {
+                int a = (e + 1) % 3, b = (e + 2) % 3; /* edge e runs a -> b, opposite vertex e */
+                int64_t dx = X[b] - X[a], dy = Y[b] - Y[a];
+                E[e] = dx * (py - Y[a]) - dy * (px - X[a]);
+                int topleft = (dy < 0) || (dy == 0 && dx > 0);
+                if (!(E[e] > 0 || (E[e] == 0 && topleft))) in = 0;
+            }
+            if (!in) continue;
+            size_t p = (size_t)j * (size_t)f->W + (size_t)i;
+            if (f->cover) f->cover[p]++;
+            float e0 = (float)E[0], e1 = (float)E[1], e2 = (float)E[2];
+            float num = fmaf(e2, iw[2], fmaf(e1, iw[1], e0 * iw[0]));
+            float depth = (float)A2 / num;
+            uint32_t dbits;
+            memcpy(&dbits, &depth, 4);
+            uint64_t k = ((uint64_t)dbits << 32) | (uint64_t)id;
+            if (k < f->key[p]) {
+                f->key[p] = k;
+                if (f->rgb) {
+                    for (int c = 0; c < 3; ++c) {
+                        float cn = fmaf(e2 * iw[2], col[2][c], fmaf(e1 * iw[1], col[1][c], (e0 * iw[0]) * col[0][c]));
+                        float v = cn / num;
+                        long q = lrintf(v);
+                        if (!(v == v)) q = 0;
+                        if (q < 0) q = 0;
+                        if (q > 255) q = 255;
+                        f->rgb[p * 3 + c] = (uint8_t)q;
+                    }
+                }
+            }
+        }
+    }
+}
+
+/* N2-N7 for one scene triangle already transformed to clip space */
+static void raster_clip_tri(oframe *f, const overt tri[3], uint32_t id)
+{
+    overt poly[MAXPOLY];
+    int n = clip_triangle(tri, poly);
+    if (n < 3) return;
+    int64_t X[MAXPOLY], Y[MAXPOLY];
+    float iw[MAXPOLY];
+    const float sx = 128.0f * (float)f->W, sy = 128.0f * (float)f->H;
+    for (int v = 0; v < n; ++v) {
+        float w = poly[v].c[3];
+        if (!(w > 0.0f)) return;
+        iw[v] = 1.0f / w;
+        float xn = poly[v].c[0] * iw[v], yn = poly[v].c[1] * iw[v];
+        float fx = fmaf(xn, sx, sx), fy = fmaf(yn, sy, sy);
+        if (!(fx >= -64.0f && fx <= 2.0f * sx + 64.0f && fy >= -64.0f && fy <= 2.0f * sy + 64.0f)) return;
+        X[v] = (int64_t)lrintf(fx);
+        Y[v] = (int64_t)lrintf(fy);
+    }
+    for (int i = 1; i + 1 < n; ++i) {
+        int64_t tx[3] = {X[0], X[i], X[i + 1]}, ty[3] = {Y[0], Y[i], Y[i + 1]};
+        float tw[3] = {iw[0], iw[i], iw[i + 1]};
+        float tc[3][3];
+        for (int c = 0; c < 3; ++c) { tc[0][c] = poly[0].col[c]; tc[1][c] = poly[i].col[c]; tc[2][c] = poly[i + 1].col[c]; }
+        raster_subtri(f, tx, ty, tw, tc, id);
+    }
+}
+
+static void render_env(oframe *f, const float *verts, const uint32_t *idx, uint32_t T, const uint8_t *colors,
+                       const float *M)
+{
+    for (uint32_t t = 0; t < T; ++t) {
+        overt tri[3];
+        for (int v = 0; v < 3; ++v) {
+            uint32_t vi = idx[3 * (size_t)t + v];
+            transform(M, verts + 3 * (size_t)vi, &tri[v]);
+            for (int c = 0; c < 3; ++c) tri[v].col[c] = colors ? (float)colors[3 * (size_t)vi + c] : 0.0f;
+        }
+        raster_clip_tri(f, tri, t);
+    }
+}
+
+/* ------------------------------------------------------------------ exported */
+
+/* Render B environments of ONE scene.  All pointers are host memory.
+ * depth [B][H][W] float, tri_id [B][H][W] uint32 (may be NULL), rgb [B][H][W][3] uint8
+ * (NULL unless colors given), cover [B][H][W] uint32 (may be NULL).
+ * nthreads <= 0 uses every core.  Returns the number of threads used. */
+int oracle_render(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
+                  const float *view_proj, uint32_t B, int H, int W, float background, float *depth,
+                  uint32_t *tri_id, uint8_t *rgb, uint32_t *cover, int nthreads)
+{
+    (void)V;
+    int used = 1;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_num_procs();
+    used = nthreads;
+#else
+    nthreads = 1;
+#endif
+    size_t npix = (size_t)H * (size_t)W;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int64_t b = 0; b < (int64_t)B; ++b) {
+        oframe f;
+        f.H = H;
+        f.W = W;
+        f.key = (uint64_t *)malloc(npix * sizeof(uint64_t));
+        for (size_t p = 0; p < npix; ++p) f.key[p] = ~(uint64_t)0;
+        f.cover = cover ? cover + (size_t)b * npix : NULL;
+        if (f.cover) memset(f.cover, 0, npix * sizeof(uint32_t));
+        f.rgb = (rgb && colors) ? rgb + (size_t)b * npix * 3 : NULL;
+        if (f.rgb) memset(f.rgb, 0, npix * 3);
+        render_env(&f, verts, idx, T, colors, view_proj + 16 * (size_t)b);
+        for (size_t p = 0; p < npix; ++p) {
+            uint64_t k = f.key[p];
+            float d = background;
+            uint32_t id = 0xFFFFFFFFu;
+            if (k != ~(uint64_t)0) {
+                uint32_t bits = (uint32_t)(k >> 32);
+                memcpy(&d, &bits, 4);
+                id = (uint32_t)(k & 0xFFFFFFFFu);
+            }
+            depth[(size_t)b * npix + p] = d;
+            if (tri_id) tri_id[(size_t)b * npix + p] = id;
+        }
+        free(f.key);
+    }
+    return used;
+}
+
+/* N5-N6 alone: coverage counts of triangles given directly in 1/256-pixel integer
+ * coordinates xy[n][3][2]; cover[H][W] is incremented.  For pinning the fill rule. */
+void oracle_cover_fixed(const int32_t *xy, uint32_t n, int H, int W, uint32_t *cover)
+{
+    size_t npix = (size_t)H * (size_t)W;
+    uint64_t *key = (uint64_t *)malloc(npix * sizeof(uint64_t));
+    for (size_t p = 0; p < npix; ++p) key[p] = ~(uint64_t)0;
+    oframe f = {H, W, key, cover, NULL};
+    for (uint32_t t = 0; t < n; ++t) {
+        int64_t X[3], Y[3];
+        float iw[3] = {1.0f, 1.0f, 1.0f};
+        float col[3][3] = {{0}};
+        for (int v = 0; v < 3; ++v) { X[v] = xy[6 * t + 2 * v]; Y[v] = xy[6 * t + 2 * v + 1]; }
+        raster_subtri(&f, X, Y, iw, col, t);
+    }
+    free(key);
+}
+
+/* N1-N3 alone: transform + clip one triangle; poly_out[MAXPOLY][4] receives clip coords.
+ * Returns the vertex count.  For pinning the clipper. */
+int oracle_clip(const float *M, const float *tri_xyz, float *poly_out)
+{
+    overt tri[3], poly[MAXPOLY];
+    for (int v = 0; v < 3; ++v) {
+        transform(M, tri_xyz + 3 * v, &tri[v]);
+        tri[v].col[0] = tri[v].col[1] = tri[v].col[2] = 0.0f;
+    }
+    int n = clip_triangle(tri, poly);
+    for (int v = 0; v < n; ++v)
+        for (int i = 0; i < 4; ++i) poly_out[4 * v + i] = poly[v].c[i];
+    return n;
+}

@@ -1,0 +1,571 @@
+"""Pins for the CPU oracle: closed forms, brute force, invariants (no GPU needed).
+
+The paper prints no renderer output to compare with (Sec. 3.2 delegates rasterisation to
+the graphics API), so the oracle is tied to things that do not depend on it: analytic
+depths of planes, a float64 ray caster, exact-integer point-in-polygon tests and a
+hand-enumerated fill-rule fixture.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from raycast import raycast
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+NOHIT = 0xFFFFFFFF
+
+
+def cam(pos=(0, 0, 0), yaw=0.0, pitch=0.0, near=0.01, far=20.0, hfov=90.0, aspect=1.0):
+    return synth.view_proj_from_pose(pos, yaw, pitch, hfov, aspect, near, far)
+
+
+def ulp_diff(a, b):
+    ai = np.asarray(a, np.float32).view(np.int32).astype(np.int64)
+    bi = np.asarray(b, np.float32).view(np.int32).astype(np.int64)
+    return np.abs(ai - bi)
+
+
+# ---------------------------------------------------------------- 1. camera-facing quad
+
+def facing_quad(d, i0, i1, j0, j1, W, H):
+    """Quad at eye distance d whose corners project onto pixel-centre lines i0,i1 / j0,j1."""
+    xn = lambda i: (i + 0.5) * 2.0 / W - 1.0
+    yn = lambda j: (j + 0.5) * 2.0 / H - 1.0
+    # camera at origin, looking down -z, y up; image y is down so world y = -yn * d
+    tl = (xn(i0) * d, -yn(j0) * d, -d)
+    tr = (xn(i1) * d, -yn(j0) * d, -d)
+    br = (xn(i1) * d, -yn(j1) * d, -d)
+    bl = (xn(i0) * d, -yn(j1) * d, -d)
+    return np.array([tl, tr, br, bl], np.float32)
+
+
+@pytest.mark.parametrize("split", ["tl-br", "tr-bl"])
+@pytest.mark.parametrize("flip", [False, True])
+@pytest.mark.parametrize("d", [2.0, 0.5, 16.0])
+def test_facing_quad_exact_rectangle_and_depth(split, flip, d):
+    H = W = 64
+    v = facing_quad(d, 8, 40, 16, 48, W, H)
+    idx = np.array([[0, 1, 2], [0, 2, 3]] if split == "tl-br" else [[0, 1, 3], [1, 2, 3]], np.uint32)
+    if flip:
+        idx = idx[:, ::-1].copy()
+    r = oracle.render_scene(v, idx, cam()[None], H, W, want_cover=True)
+    covered = r["tri_id"][0] != NOHIT
+    expect = np.zeros((H, W), bool)
+    expect[16:48, 8:40] = True          # left/top boundary pixels in, right/bottom out
+    assert np.array_equal(covered, expect)
+    assert covered.sum() == 32 * 32
+    assert np.array_equal(r["cover"][0], expect.astype(np.uint32))   # diagonal pixels exactly once
+    assert ulp_diff(r["depth"][0][expect], np.float32(d)).max() <= 4
+    assert np.all(r["depth"][0][~expect] == 0.0)
+
+
+@pytest.mark.parametrize("side", ["left", "right", "top", "bottom"])
+def test_facing_quad_clipped_by_each_side_plane(side):
+    H = W = 64
+    d = 2.0
+    v = facing_quad(d, 8, 40, 16, 48, W, H)
+    expect = np.zeros((H, W), bool)
+    if side == "left":
+        v[[0, 3], 0] = -3.0 * d
+        expect[16:48, 0:40] = True
+    elif side == "right":
+        v[[1, 2], 0] = 3.0 * d
+        expect[16:48, 8:64] = True
+    elif side == "top":
+        v[[0, 1], 1] = 3.0 * d
+        expect[0:48, 8:40] = True
+    else:
+        v[[2, 3], 1] = -3.0 * d
+        expect[16:64, 8:40] = True
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    r = oracle.render_scene(v, idx, cam()[None], H, W, want_cover=True)
+    assert np.array_equal(r["tri_id"][0] != NOHIT, expect)
+    assert r["cover"][0].max() == 1
+    assert ulp_diff(r["depth"][0][expect], np.float32(d)).max() <= 4
+
+
+@pytest.mark.parametrize("d,visible", [(0.0101, True), (0.0099, False), (19.99, True), (20.01, False)])
+def test_facing_quad_near_and_far_limits(d, visible):
+    H = W = 32
+    v = facing_quad(d, 4, 20, 4, 20, W, H)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    r = oracle.render_scene(v, idx, cam()[None], H, W)
+    n = int((r["tri_id"][0] != NOHIT).sum())
+    if visible:
+        assert n == 16 * 16
+        assert np.allclose(r["depth"][0][4:20, 4:20], d, rtol=1e-5)
+    else:
+        assert n == 0
+
+
+def test_background_value_and_miss_id():
+    v = facing_quad(2.0, 2, 6, 2, 6, 16, 16)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    r = oracle.render_scene(v, idx, cam()[None], 16, 16, background=7.5)
+    miss = r["tri_id"][0] == NOHIT
+    assert miss.sum() == 256 - 16
+    assert np.all(r["depth"][0][miss] == np.float32(7.5))
+
+
+# ---------------------------------------------------------------- 2. floor / sloped planes
+
+@pytest.mark.parametrize("H,W", [(64, 64), (32, 64)])
+def test_level_camera_over_floor_is_perspective_correct(H, W):
+    h = 1.25
+    far = 200.0
+    S = 150.0
+    v = np.array([[-S, 0, -S], [S, 0, -S], [S, 0, S], [-S, 0, S]], np.float32)   # two huge triangles
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    aspect = W / H
+    M = cam(pos=(0.3, h, -0.2), yaw=0.7, far=far, aspect=aspect)
+    r = oracle.render_scene(v, idx, M[None], H, W)
+    tan_v = 1.0                                     # hFoV 90 and P[1][1] = -f*aspect: y_n = -y_e * aspect / d
+    for j in range(H):
+        yn = (j + 0.5) * 2.0 / H - 1.0
+        row = r["depth"][0, j]
+        if yn <= 0:
+            assert np.all(r["tri_id"][0, j] == NOHIT)
+            continue
+        expect = h * aspect / (yn * tan_v)
+        if expect < far * 0.7:                       # rows whose floor point is inside the patch and far plane
+            # vertices are snapped to 1/256 px: a row k pixels below the horizon shifts by about 1/(256 k)
+            rtol = 2.0 * (1.0 / 256.0) / (j + 0.5 - H / 2) + 1e-5
+            assert np.allclose(row, expect, rtol=rtol), (j, row.min(), row.max(), expect)
+
+
+def test_sloped_plane_against_raycast_depth_with_large_triangles():
+    # One large tilted triangle pair: affine interpolation of w would be off by far more than 1e-3.
+    v = np.array([[-4, -1, -1.0], [4, -1.5, -2.0], [5, 3, -9.0], [-5, 2.5, -8.0]], np.float32)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    M = cam()
+    r = oracle.render_scene(v, idx, M[None], 64, 64)
+    ids, dep, _ = raycast(v, idx, M, 64, 64)
+    hit = ids[0] >= 0
+    both = hit & (r["tri_id"][0] != NOHIT)
+    assert both.sum() > 1500
+    assert np.allclose(r["depth"][0][both], dep[0][both], rtol=1e-3)
+
+
+# ---------------------------------------------------------------- 3. brute-force ray casting
+
+def random_soup(rng, n, spread=3.0, zmin=-8.0, zmax=1.0, size=2.0):
+    c = np.stack([rng.uniform(-spread, spread, n), rng.uniform(-spread, spread, n), rng.uniform(zmin, zmax, n)], 1)
+    v = c[:, None, :] + rng.uniform(-size, size, (n, 3, 3))
+    return v.reshape(-1, 3).astype(np.float32), np.arange(3 * n, dtype=np.uint32).reshape(n, 3)
+
+
+@pytest.mark.parametrize("seed,n,res", [(0, 40, 16), (1, 120, 32), (2, 200, 64), (3, 60, 64), (4, 200, 16)])
+def test_random_soup_matches_raycast(seed, n, res):
+    """Triangles cross the near plane and every side plane; ids must agree wherever the
+    ray-cast answer is stable under a 2/256-pixel nudge, depths to 1e-3."""
+    rng = np.random.default_rng(seed)
+    v, idx = random_soup(rng, n)
+    M = cam(pos=(0.1, -0.2, 0.5), yaw=0.2 * seed, pitch=0.1 * (seed - 2), near=0.05, far=12.0)
+    r = oracle.render_scene(v, idx, M[None], res, res)
+    e = 2.0 / 256.0
+    ids, dep, gap = raycast(v, idx, M, res, res, offsets=((0, 0), (e, 0), (-e, 0), (0, e), (0, -e)))
+    stable = np.all(ids == ids[0:1], axis=0) & np.all(gap > 1e-4, axis=0)
+    assert stable.mean() > 0.85
+    oid = r["tri_id"][0].astype(np.int64)
+    oid[oid == NOHIT] = -1
+    assert np.array_equal(oid[stable], ids[0][stable])
+    hit = stable & (ids[0] >= 0)
+    assert hit.sum() > 0.2 * res * res
+    # vertex snapping moves a steep triangle's plane by about what a 2/256-px nudge of the ray does
+    with np.errstate(invalid="ignore"):
+        slack = 2.0 * np.abs(dep[1:] - dep[0:1]).max(axis=0) + 1e-4 * dep[0]
+    assert np.all(np.abs(r["depth"][0] - dep[0])[hit] <= slack[hit])
+    assert np.allclose(r["depth"][0][hit], dep[0][hit], rtol=1e-2)
+
+
+def test_room_scene_matches_raycast_subset():
+    """A slice of the smallest benchmark scene through the same check (one camera, 32x32)."""
+    w = synth.build_config(1, B=2, scale=0.06)
+    s = w.scenes[0]
+    M = w.view_proj[1]
+    r = oracle.render_scene(s.vertices, s.indices, M[None], 32, 32)
+    e = 2.0 / 256.0
+    ids, dep, gap = raycast(s.vertices, s.indices, M, 32, 32, offsets=((0, 0), (e, 0), (-e, 0), (0, e), (0, -e)))
+    # adjacent coplanar triangles are legitimately ambiguous at shared edges only; the nudge test removes them
+    stable = np.all(ids == ids[0:1], axis=0) & np.all(gap > 1e-4, axis=0)
+    oid = r["tri_id"][0].astype(np.int64)
+    oid[oid == NOHIT] = -1
+    assert stable.mean() > 0.5
+    assert np.array_equal(oid[stable], ids[0][stable])
+    assert np.allclose(r["depth"][0][stable], dep[0][stable], rtol=1e-3)
+
+
+# ---------------------------------------------------------------- 4. fill rule and watertightness
+
+def load_golden(name):
+    tris, rows = [], []
+    with open(os.path.join(HERE, "golden", name)) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line.startswith("tri"):
+                tris.append([int(t) for t in line.split()[1:]])
+            else:
+                rows.append([int(ch) for ch in line])
+    return np.array(tris, np.int32).reshape(-1, 3, 2), np.array(rows, np.uint32)
+
+
+@pytest.mark.parametrize("name", ["fill_rule_upper_left.txt", "fill_rule_lower_right.txt",
+                                  "fill_rule_centre_corners.txt"])
+def test_hand_enumerated_fill_rule(name):
+    tris, expect = load_golden(name)
+    got = oracle.cover_fixed(tris, expect.shape[0], expect.shape[1])
+    assert np.array_equal(got, expect)
+    # vertex order and winding must not matter
+    for perm in ([1, 2, 0], [2, 0, 1], [0, 2, 1], [2, 1, 0], [1, 0, 2]):
+        assert np.array_equal(oracle.cover_fixed(tris[:, perm, :], *expect.shape), expect)
+
+
+def strictly_inside_convex(poly, px, py):
+    """Exact integer test: strictly inside / strictly outside a convex polygon (any winding)."""
+    poly = [(int(x), int(y)) for x, y in poly]
+    n = len(poly)
+    signs = []
+    for k in range(n):
+        (x0, y0), (x1, y1) = poly[k], poly[(k + 1) % n]
+        signs.append((x1 - x0) * (py - y0) - (y1 - y0) * (px - x0))
+    signs = np.array(signs)
+    inside = np.all(signs > 0, axis=0) | np.all(signs < 0, axis=0)
+    outside = (np.any(signs > 0, axis=0) & np.any(signs < 0, axis=0))
+    return inside, outside
+
+
+def test_shared_edge_pairs_cover_each_pixel_once():
+    rng = np.random.default_rng(11)
+    H = W = 16
+    jj, ii = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    px, py = 256 * ii + 128, 256 * jj + 128
+    checked = 0
+    for trial in range(1500):
+        # convex quad = two triangles sharing the diagonal a-c; snap some vertices onto pixel centres
+        while True:
+            q = rng.integers(-300, 256 * W + 300, size=(4, 2))
+            if trial % 3 == 0:
+                q = (q // 256) * 256 + 128
+            elif trial % 3 == 1:
+                q[:, 0] = (q[:, 0] // 128) * 128
+            c = [int((q[(k + 1) % 4, 0] - q[k, 0]) * (q[(k + 2) % 4, 1] - q[(k + 1) % 4, 1])
+                     - (q[(k + 1) % 4, 1] - q[k, 1]) * (q[(k + 2) % 4, 0] - q[(k + 1) % 4, 0])) for k in range(4)]
+            if all(x > 0 for x in c) or all(x < 0 for x in c):
+                break
+        tris = np.array([[q[0], q[1], q[2]], [q[0], q[2], q[3]]])
+        cover = oracle.cover_fixed(tris, H, W)
+        inside, outside = strictly_inside_convex(q, px, py)
+        assert cover.max() <= 1, trial
+        assert np.all(cover[inside] == 1), trial
+        assert np.all(cover[outside] == 0), trial
+        checked += int(inside.sum())
+    assert checked > 20000
+
+
+def test_fans_and_jittered_grids_are_watertight():
+    rng = np.random.default_rng(5)
+    H = W = 24
+    jj, ii = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    px, py = 256 * ii + 128, 256 * jj + 128
+    n_fans = n_grids = 0
+    # (a) fan around an interior vertex of a convex polygon
+    for trial in range(300):
+        n = int(rng.integers(3, 12))
+        ang = np.sort(rng.uniform(0, 2 * np.pi, n))
+        rad = rng.uniform(500, 2800)
+        c = rng.integers(2000, 4000, 2)
+        poly = np.stack([c[0] + rad * np.cos(ang), c[1] + rad * np.sin(ang)], 1).round().astype(np.int64)
+        if trial % 2:
+            poly = (poly // 128) * 128
+            c = (c // 128) * 128
+        cr = [(poly[(k + 1) % n] - poly[k]) for k in range(n)]
+        z = [int(cr[k][0] * cr[(k + 1) % n][1] - cr[k][1] * cr[(k + 1) % n][0]) for k in range(n)]
+        ins_c, _ = strictly_inside_convex(poly, np.array([c[0]]), np.array([c[1]]))
+        if not (all(v > 0 for v in z) and ins_c[0]):
+            continue
+        tris = np.array([[c, poly[k], poly[(k + 1) % n]] for k in range(n)])
+        cover = oracle.cover_fixed(tris, H, W)
+        inside, outside = strictly_inside_convex(poly, px, py)
+        assert cover.max() <= 1
+        assert np.all(cover[inside] == 1) and np.all(cover[outside] == 0)
+        n_fans += 1
+    # (b) jittered grid with random diagonals; boundary is an axis-aligned rectangle
+    for trial in range(40):
+        n = 9
+        base = np.arange(n + 1) * 600 + 200
+        gx, gy = np.meshgrid(base, base)
+        jit = rng.integers(-250, 251, size=(n + 1, n + 1, 2))
+        jit[0, :], jit[-1, :], jit[:, 0], jit[:, -1] = 0, 0, 0, 0
+        P = np.stack([gx + jit[..., 0], gy + jit[..., 1]], -1)
+        if trial % 2:
+            P = (P // 64) * 64
+        tris = []
+        for r in range(n):
+            for q in range(n):
+                a, b, c2, d = P[r, q], P[r, q + 1], P[r + 1, q + 1], P[r + 1, q]
+                tris += [[a, b, c2], [a, c2, d]] if rng.integers(0, 2) else [[a, b, d], [b, c2, d]]
+        tris = np.array(tris)
+        a2 = ((tris[:, 1, 0] - tris[:, 0, 0]) * (tris[:, 2, 1] - tris[:, 0, 1])
+              - (tris[:, 2, 0] - tris[:, 0, 0]) * (tris[:, 1, 1] - tris[:, 0, 1]))
+        if np.any(a2 <= 0):          # a jitter folded a cell over: not a valid planar mesh
+            continue
+        cover = oracle.cover_fixed(tris, H, W)
+        rect = np.array([P[0, 0], P[0, -1], P[-1, -1], P[-1, 0]])
+        inside, outside = strictly_inside_convex(rect, px, py)
+        assert cover.max() <= 1
+        assert np.all(cover[inside] == 1) and np.all(cover[outside] == 0)
+        n_grids += 1
+    assert n_fans > 100 and n_grids > 20
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_jittered_wall_through_clipper_is_watertight(seed):
+    """A tessellated plane filling the whole view, straddling every side plane and (for
+    oblique close cameras) the near plane: every pixel is covered exactly once, which
+    pins the canonical inside->outside interpolation of the clipper."""
+    rng = np.random.default_rng(100 + seed)
+    n = 26
+    u = np.linspace(-30, 30, n + 1)
+    U, Vv = np.meshgrid(u, u)
+    jit = rng.uniform(-0.3, 0.3, size=(n + 1, n + 1, 2))
+    jit[0, :], jit[-1, :], jit[:, 0], jit[:, -1] = 0, 0, 0, 0
+    P = np.stack([U + jit[..., 0], Vv + jit[..., 1], np.full_like(U, -3.0)], -1).reshape(-1, 3).astype(np.float32)
+    a = (np.arange(n)[:, None] * (n + 1) + np.arange(n)[None, :]).ravel()
+    flip = rng.integers(0, 2, a.size).astype(bool)
+    t1 = np.where(flip[:, None], np.stack([a, a + 1, a + n + 1], 1), np.stack([a, a + 1, a + n + 2], 1))
+    t2 = np.where(flip[:, None], np.stack([a + 1, a + n + 2, a + n + 1], 1), np.stack([a, a + n + 2, a + n + 1], 1))
+    idx = np.concatenate([t1, t2], 0).astype(np.uint32)
+    e = 2.0 / 256.0
+    offs = ((0, 0), (e, 0), (-e, 0), (0, e), (0, -e))
+    n_hit = 0
+    for k in range(4):
+        pos = (rng.uniform(-5, 5), rng.uniform(-5, 5), rng.uniform(-2.93, 0.0))
+        yaw, pitch = rng.uniform(-1.0, 1.0), rng.uniform(-0.8, 0.8)
+        M = cam(pos=pos, yaw=yaw, pitch=pitch, near=0.05, far=500.0)
+        r = oracle.render_scene(P, idx, M[None], 32, 32, want_cover=True)
+        ids, _, _ = raycast(P, idx, M, 32, 32, offsets=offs)
+        hit_all = np.all(ids >= 0, axis=0)
+        miss_all = np.all(ids < 0, axis=0)
+        assert r["cover"][0].max() <= 1                       # never twice, anywhere
+        assert np.all(r["cover"][0][hit_all] == 1)            # no cracks
+        assert np.all(r["cover"][0][miss_all] == 0)
+        n_hit += int(hit_all.sum())
+    assert n_hit > 2500
+
+
+# ---------------------------------------------------------------- 5. invariants
+
+def small_workload():
+    w = synth.build_config(1, B=4)
+    return w, w.scenes[0]
+
+
+def test_closed_room_has_no_background_and_depth_in_range():
+    w, s = small_workload()
+    r = oracle.render_scene(s.vertices, s.indices, w.view_proj, 64, 64)
+    assert (r["tri_id"] == NOHIT).sum() == 0
+    assert r["depth"].min() >= 0.01
+    assert r["depth"].max() <= 20.0 * (1 + 1e-6)
+    assert r["depth"].max() <= math.sqrt(10 ** 2 + 8 ** 2 + 3 ** 2)
+
+
+def test_index_permutation_permutes_ids_only():
+    w, s = small_workload()
+    r0 = oracle.render_scene(s.vertices, s.indices, w.view_proj, 64, 64)
+    perm = np.random.default_rng(3).permutation(s.T)
+    r1 = oracle.render_scene(s.vertices, s.indices[perm], w.view_proj, 64, 64)
+    same_depth = r0["depth"] == r1["depth"]
+    assert same_depth.all()                       # depth is the minimum either way
+    mapped = perm[r1["tri_id"]]
+    differ = mapped != r0["tri_id"]
+    # ids may differ only where two triangles tie exactly in depth
+    assert differ.mean() < 0.02
+
+
+def test_vertex_rotation_within_triangles_keeps_coverage():
+    w, s = small_workload()
+    r0 = oracle.render_scene(s.vertices, s.indices, w.view_proj, 64, 64, want_cover=True)
+    rolled = np.roll(s.indices, 1, axis=1)
+    r1 = oracle.render_scene(s.vertices, rolled, w.view_proj, 64, 64, want_cover=True)
+    assert np.array_equal(r0["cover"], r1["cover"])
+    assert np.array_equal(r0["tri_id"], r1["tri_id"])
+    # a clipped triangle fans from a different vertex after rotation; the snapped pieces then
+    # span slightly different planes (most visibly on slivers seen edge-on), so depth agrees
+    # closely but not to the last bits; unclipped triangles must agree to rounding
+    assert np.allclose(r0["depth"], r1["depth"], rtol=1e-3)
+    assert np.mean(np.abs(r0["depth"] - r1["depth"]) > 1e-5 * r0["depth"]) < 0.05
+
+
+def test_exact_depth_tie_goes_to_lower_triangle_id():
+    v = facing_quad(2.0, 2, 10, 2, 10, 16, 16)
+    idx = np.array([[0, 1, 2], [0, 2, 3], [0, 1, 2], [0, 2, 3]], np.uint32)   # every triangle twice
+    r = oracle.render_scene(v, idx, cam()[None], 16, 16, want_cover=True)
+    hit = r["tri_id"][0] != NOHIT
+    assert hit.sum() == 64
+    assert r["tri_id"][0][hit].max() <= 1
+    assert np.all(r["cover"][0][hit] == 2)
+
+
+def test_degenerate_hidden_and_subpixel_triangles_contribute_nothing():
+    M = cam()
+    v = np.array([
+        [0, 0, -2], [1, 1, -2], [2, 2, -2],                 # zero area
+        [0, 0, 3], [1, 0, 3], [0, 1, 3],                    # behind the camera
+        [0.001, 0.001, -2], [0.004, 0.001, -2], [0.001, 0.004, -2],   # between pixel centres
+        [50, 0, -2], [51, 0, -2], [50, 1, -2],              # outside the right plane
+        [np.nan, 0, -2], [1, 0, -2], [0, 1, -2],            # non-finite vertex
+    ], np.float32)
+    idx = np.arange(15, dtype=np.uint32).reshape(5, 3)
+    r = oracle.render_scene(v, idx, M[None], 64, 64)
+    assert (r["tri_id"] != NOHIT).sum() == 0
+
+
+def test_nearer_triangle_wins_and_orthographic_depth_is_affine():
+    # orthographic matrix (w == 1): depth must be exactly 1 everywhere, ids decided by the tie rule
+    M = np.array([[0.25, 0, 0, 0], [0, 0.25, 0, 0], [0, 0, -0.1, 0], [0, 0, 0, 1]], np.float32)
+    v = np.array([[-2, -2, -1], [2, -2, -1], [0, 3, -1], [-3, -1, -5], [3, -1, -5], [0, 2, -5]], np.float32)
+    idx = np.array([[3, 4, 5], [0, 1, 2]], np.uint32)
+    r = oracle.render_scene(v, idx, M[None], 32, 32)
+    hit = r["tri_id"][0] != NOHIT
+    assert hit.sum() > 100
+    assert np.all(r["depth"][0][hit] == 1.0)
+    # perspective: put triangle 1 nearer than triangle 0 -> it must win wherever both cover
+    Mp = cam()
+    r2 = oracle.render_scene(v, idx, Mp[None], 32, 32, want_cover=True)
+    both = r2["cover"][0] == 2
+    assert both.sum() > 5
+    assert np.all(r2["tri_id"][0][both] == 1)
+    assert np.allclose(r2["depth"][0][both], 1.0, rtol=1e-5)
+
+
+def test_clipper_output_lies_in_the_frustum_and_keeps_plane_area():
+    """The clipped polygon of a camera-facing triangle has the area of (triangle ∩ view square)."""
+    rng = np.random.default_rng(8)
+    M = cam()
+    d = 2.0
+    for _ in range(200):
+        tri = np.concatenate([rng.uniform(-3 * d, 3 * d, (3, 2)), np.full((3, 1), -d)], 1).astype(np.float32)
+        poly = oracle.clip(M, tri)
+        # reference area: float64 half-plane cuts of the triangle against the view square, written separately
+        ref_area = _clip_area_reference(tri[:, :2].astype(np.float64), d)
+        if poly.shape[0] == 0:
+            assert ref_area < 1e-6
+            continue
+        assert np.all(np.abs(poly[:, 0]) <= poly[:, 3] * (1 + 1e-5))
+        assert np.all(np.abs(poly[:, 1]) <= poly[:, 3] * (1 + 1e-5))
+        xy = poly[:, :2].astype(np.float64)
+        area = 0.5 * abs(np.sum(xy[:, 0] * np.roll(xy[:, 1], -1) - np.roll(xy[:, 0], -1) * xy[:, 1]))
+        assert abs(area - ref_area) <= 1e-4 * max(1.0, ref_area)
+
+
+def _clip_area_reference(tri, d):
+    """Area of triangle ∩ [-d,d]^2 in float64 by successive half-plane cuts."""
+    poly = [tuple(p) for p in tri]
+    for axis, sign in ((0, 1), (0, -1), (1, 1), (1, -1)):
+        out = []
+        for i in range(len(poly)):
+            a, b = poly[i], poly[(i + 1) % len(poly)]
+            da, db = d - sign * a[axis], d - sign * b[axis]
+            if da >= 0:
+                out.append(a)
+            if (da >= 0) != (db >= 0):
+                t = da / (da - db)
+                out.append((a[0] + t * (b[0] - a[0]), a[1] + t * (b[1] - a[1])))
+        poly = out
+        if len(poly) < 3:
+            return 0.0
+    xy = np.array(poly)
+    return 0.5 * abs(np.sum(xy[:, 0] * np.roll(xy[:, 1], -1) - np.roll(xy[:, 0], -1) * xy[:, 1]))
+
+
+def test_colour_interpolation_constant_and_linear():
+    """Constant vertex colour stays constant; on a camera-facing quad colour is affine in the pixel index."""
+    H = W = 32
+    v = facing_quad(2.0, 0, 31, 0, 31, W, H)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    col = np.array([[10, 200, 30]] * 4, np.uint8)
+    r = oracle.render_scene(v, idx, cam()[None], H, W, colors=col)
+    hit = r["tri_id"][0] != NOHIT
+    assert np.all(r["rgb"][0][hit] == np.array([10, 200, 30], np.uint8))
+    col = np.array([[0, 0, 0], [248, 0, 0], [248, 248, 0], [0, 248, 0]], np.uint8)   # r = 8 i, g = 8 j
+    r = oracle.render_scene(v, idx, cam()[None], H, W, colors=col)
+    jj, ii = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    assert np.all(np.abs(r["rgb"][0][..., 0].astype(int) - 8 * ii)[hit] <= 1)
+    assert np.all(np.abs(r["rgb"][0][..., 1].astype(int) - 8 * jj)[hit] <= 1)
+    assert np.all(r["rgb"][0][..., 2][hit] == 0)
+
+
+def test_colour_is_perspective_correct_on_a_receding_plane():
+    # floor quad receding from the camera; colour r encodes world z; compare with the ray-cast hit point
+    v = np.array([[-50, -1, 0], [50, -1, 0], [50, -1, -25.5], [-50, -1, -25.5]], np.float32)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    col = np.array([[0, 0, 0], [0, 0, 0], [255, 0, 0], [255, 0, 0]], np.uint8)       # r = -10 z
+    M = cam(far=100.0)
+    r = oracle.render_scene(v, idx, M[None], 64, 64, colors=col)
+    hit = r["tri_id"][0] != NOHIT
+    # hit point on the plane y = -1 along the view axis: z = -depth
+    expect = np.clip(np.rint(10.0 * r["depth"][0]), 0, 255)
+    assert hit.sum() > 1000
+    assert np.all(np.abs(r["rgb"][0][..., 0].astype(int) - expect.astype(int))[hit] <= 1)
+
+
+# ---------------------------------------------------------------- 6. snapping and canonical clipping
+
+@pytest.mark.parametrize("frac,left_in", [(0.25, True), (0.75, False), (-0.25, True), (-0.75, True)])
+def test_snapping_rounds_to_nearest_subpixel(frac, left_in):
+    """A quad edge `frac`/256 px right of a pixel-centre line snaps to the nearest 1/256 px:
+    +0.25 -> onto the line (pixel kept by the left-edge rule), +0.75 -> one unit right (pixel lost);
+    truncation or floor instead of rounding would flip one of these cases."""
+    H = W = 64
+    d = 2.0
+    v = facing_quad(d, 8, 40, 16, 48, W, H)
+    fx = 256.0 * 8 + 128.0 + frac                      # wanted un-rounded coordinate, exact in binary32
+    x = (fx / (128.0 * W) - 1.0) * d
+    v[[0, 3], 0] = x
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    r = oracle.render_scene(v, idx, cam()[None], H, W)
+    col8 = r["tri_id"][0][16:48, 8] != NOHIT
+    assert np.all(col8 == left_in)
+    assert np.all(r["tri_id"][0][16:48, 9] != NOHIT)
+    assert np.all(r["tri_id"][0][16:48, 7] == NOHIT) or frac < -0.5   # -0.75 snaps one unit left: still right of centre 7
+
+
+def test_clipper_generates_bit_identical_points_on_shared_edges():
+    """Two triangles sharing edge PQ, walked in opposite directions, must produce the very same
+    crossing point where PQ leaves the frustum (interpolation always runs inside -> outside)."""
+    rng = np.random.default_rng(21)
+    M = cam(pos=(0.2, 0.1, 0.3), yaw=0.3, pitch=-0.2, near=0.5, far=9.0)
+    found = 0
+    for _ in range(400):
+        P = np.array([rng.uniform(-1, 1), rng.uniform(-1, 1), rng.uniform(-6, -2)], np.float32)     # inside
+        Q = P + rng.uniform(-12, 12, 3).astype(np.float32)                                          # mostly outside
+        R1 = P + rng.uniform(-1, 1, 3).astype(np.float32)
+        R2 = P + rng.uniform(-1, 1, 3).astype(np.float32)
+        a = oracle.clip(M, np.stack([P, Q, R1]))
+        b = oracle.clip(M, np.stack([Q, P, R2]))
+        c = oracle.clip(M, np.stack([R2, Q, P]))
+        if a.shape[0] <= 3 or b.shape[0] <= 3:
+            continue
+        # every generated point on PQ seen by one triangle must be seen, bit for bit, by the others
+        pq = [{row.tobytes() for row in poly if _on_segment(row, M, P, Q)} for poly in (a, b, c)]
+        assert pq[0] == pq[1] == pq[2]
+        found += bool(pq[0])
+    assert found > 100
+
+
+def _on_segment(g, M, P, Q):
+    """Is clip-space point g (approximately) on the image of segment PQ and not an endpoint?"""
+    M = M.astype(np.float64)
+    p = M @ np.append(P.astype(np.float64), 1.0)
+    q = M @ np.append(Q.astype(np.float64), 1.0)
+    d = q - p
+    t = np.dot(g.astype(np.float64) - p, d) / np.dot(d, d)
+    if not (1e-4 < t < 1 - 1e-4):
+        return False
+    return np.linalg.norm(p + t * d - g) <= 1e-4 * (1 + np.linalg.norm(g))
