@@ -1,0 +1,110 @@
+/*
+ * bps.h -- C ABI of the batch renderer for large-batch simulation on AMD MI355X (gfx950).
+ *
+ * The operation (paper Sec. 3, Fig. 2, Sec. 3.2 "Batch Rendering"): a batch of N environment
+ * states goes in as ONE request, N low-resolution frames come out in GPU memory; the K << N
+ * scene assets are uploaded once and every environment refers to one of them by id
+ * (Sec. 3.2 "Scene asset sharing").  Here an environment state is a scene handle plus a 4x4
+ * view-projection matrix and a frame is H x W float32 eye depth (optionally RGB-D).
+ *
+ * The paper leaves rasterisation to the graphics API; this library fixes the rule:
+ *   clip = M * (x, y, z, 1)^T with M row-major, normalised x right, y DOWN, z in [0,1];
+ *   triangles are clipped against the six planes |x| <= w, |y| <= w, 0 <= z <= w;
+ *   screen positions are snapped to 1/256 pixel; a pixel belongs to a triangle when its centre
+ *   passes the three integer edge tests under the top-left fill rule (two-sided, no culling by
+ *   winding); depth is perspective-correct clip-space w; the frame keeps, per pixel, the
+ *   minimum of (depth bits << 32 | triangle id), i.e. nearest surface, ties to the lower id.
+ *
+ * All functions return a status; none throws or aborts.  Unless stated otherwise pointers are
+ * HOST memory.  A renderer must be driven by one thread at a time; different renderers are
+ * independent.  There is no CPU fallback: without a usable GPU bps_create fails.
+ */
+#ifndef BPS_H
+#define BPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bps_renderer bps_renderer; /* opaque; bound to one device and one frame format */
+typedef int32_t bps_scene;                /* handle >= 0 */
+typedef int32_t bps_status;
+
+enum {
+    BPS_OK = 0,
+    BPS_ERR_INVALID_ARG = -1,     /* null pointer, zero size, bad resolution, index out of range ... */
+    BPS_ERR_BAD_HANDLE = -2,      /* scene handle not live in this renderer */
+    BPS_ERR_OOM = -3,             /* host or device allocation failed */
+    BPS_ERR_HIP = -4,             /* a HIP runtime call failed; text in bps_last_error */
+    BPS_ERR_UNSUPPORTED = -5      /* frame does not fit the on-chip visibility buffer of this device */
+};
+
+enum { BPS_MODE_DEPTH = 0, BPS_MODE_RGBD = 1 };
+
+typedef struct {
+    int32_t device;          /* HIP device ordinal */
+    int32_t max_batch;       /* largest B accepted by bps_render (>= 1) */
+    int32_t height, width;   /* frame size; multiples of 8, 8..128 */
+    int32_t mode;            /* BPS_MODE_DEPTH or BPS_MODE_RGBD */
+    float background_depth;  /* written where no triangle covers the pixel centre */
+    int32_t splits;          /* work-groups per environment; 0 = choose from B and the device */
+    int32_t threads;         /* work-group size: 0 = default, else 256, 512 or 1024 */
+} bps_config;
+
+/* Create a renderer on cfg->device.  *out receives the handle.  Allocates the device scene
+ * table, the request staging ring and (lazily) the global visibility buffer used when an
+ * environment is split over several work-groups. */
+bps_status bps_create(const bps_config *cfg, bps_renderer **out);
+
+/* Waits for the device, frees every scene and buffer.  NULL is ignored. */
+void bps_destroy(bps_renderer *r);
+
+/* Scene asset upload (Sec. 3.2 "Scene asset sharing": K unique assets resident in GPU memory,
+ * referenced by many environments).
+ *   vertices  float32 [V][3]  world positions
+ *   indices   uint32  [T][3]  vertex indices; triangle id = row number
+ *   colors    uint8   [V][3]  per-vertex RGB or NULL (required for RGB-D rendering)
+ * The mesh is validated (every index < V, every coordinate finite), re-packed on the host into
+ * clusters of <= 64 vertices / <= 128 triangles, and copied to the device; the caller may free
+ * its arrays on return.  Synchronous.  *out_handle receives the scene id. */
+bps_status bps_load_scene(bps_renderer *r, const float *vertices, uint32_t V, const uint32_t *indices, uint32_t T,
+                          const uint8_t *colors, bps_scene *out_handle);
+
+/* Frees a scene.  The caller must not unload a scene that queued renders still use. */
+bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
+
+/* One batched render request (Sec. 3: "the renderer processes the batch of environment states
+ * by simultaneously rendering N frames and exposing the result directly in GPU memory").
+ *   scene_ids   host   int32 [B]          scene of each environment
+ *   view_proj   host or device float32 [B][4][4], row-major
+ *   out_depth   DEVICE float32 [B][H][W]  eye depth, background_depth where nothing is hit
+ *   out_rgb     DEVICE uint8 [B][H][W][3] or NULL; required in RGB-D mode
+ *   out_tri_id  DEVICE uint32 [B][H][W] or NULL; winning triangle id, 0xFFFFFFFF = none
+ *   stream      hipStream_t (NULL = default stream)
+ * Only enqueues work on `stream` and returns; host arrays are consumed before return, output
+ * buffers must stay alive until the stream reaches the end of the request. */
+bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
+                      float *out_depth, uint8_t *out_rgb, uint32_t *out_tri_id, void *stream);
+
+/* Timing aid for benchmarks: when enabled, bps_render brackets its rasterisation kernel with
+ * HIP events on the caller's stream.  bps_last_kernel_ms waits for those events and returns the
+ * kernel's duration in milliseconds for the most recent request. */
+bps_status bps_set_profiling(bps_renderer *r, int32_t enable);
+bps_status bps_last_kernel_ms(bps_renderer *r, float *ms);
+
+/* Facts about a loaded scene and the launch plan, for benchmarks and tests.
+ * what: 0 = clusters in the scene, 1 = triangles, 2 = vertices, 3 = device bytes held,
+ *       4 = splits used by the last request, 5 = work-groups of the last request,
+ *       6 = work-group size, 7 = LDS bytes per work-group. */
+bps_status bps_query(bps_renderer *r, bps_scene scene, int32_t what, uint64_t *value);
+
+/* Text of the last error on this renderer (owned by the renderer; never NULL).
+ * With r == NULL returns the text of the last failed bps_create on this thread. */
+const char *bps_last_error(const bps_renderer *r);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPS_H */

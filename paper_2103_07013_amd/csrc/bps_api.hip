@@ -1,0 +1,436 @@
+// Host side of the C ABI declared in include/bps.h: renderer object, scene table, request
+// staging and launch planning.  All rendering arithmetic is in raster_kernels.hip.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/bps.h"
+#include "clusters.h"
+#include "raster_kernels.h"
+
+namespace {
+
+constexpr int kMaxScenes = 4096;
+constexpr int kRing = 4;          // request staging slots in flight
+constexpr int kXcds = 8;          // work-groups are dealt round-robin to 8 accelerator dies
+
+thread_local std::string g_create_error = "";
+
+struct HostScene {
+    bool live = false;
+    bps::SceneDev dev{};
+    void* allocs[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    uint64_t bytes = 0;
+    bool has_colors = false;
+};
+
+struct RingSlot {
+    unsigned char* host = nullptr;   // pinned
+    unsigned char* dev = nullptr;
+    size_t capacity = 0;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+
+}  // namespace
+
+struct bps_renderer {
+    bps_config cfg{};
+    int device = 0;
+    int num_cu = 0;
+    int threads = 512;
+    size_t lds = 0;
+    size_t max_lds = 0;
+    std::string error = "";
+    std::vector<HostScene> scenes;
+    bps::SceneDev* d_scenes = nullptr;
+    RingSlot ring[kRing];
+    int ring_next = 0;
+    unsigned long long* gvis = nullptr;   // [max_batch][H][W], only for split frames
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    bool profiling = false, timed = false;
+    // cached plan: valid while the scene ids and split count repeat
+    std::vector<bps_scene> plan_ids;
+    int plan_splits = 0;
+    std::vector<bps::WorkItem> plan_items;
+    uint64_t last_splits = 0, last_groups = 0;
+};
+
+namespace {
+
+bps_status fail(bps_renderer* r, bps_status code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    if (r) r->error = buf; else g_create_error = buf;
+    return code;
+}
+
+#define BPS_HIP(r, call)                                                                      \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail((r), e_ == hipErrorOutOfMemory ? BPS_ERR_OOM : BPS_ERR_HIP, "%s: %s", \
+                        #call, hipGetErrorString(e_));                                        \
+    } while (0)
+
+void free_scene(HostScene& s) {
+    for (void*& p : s.allocs) {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    }
+    s = HostScene{};
+}
+
+// Choose how many work-groups share one environment: enough groups to fill the device a few
+// times over when the batch is small, one group per environment when the batch is large.
+int plan_splits(const bps_renderer* r, uint32_t B, uint32_t min_clusters) {
+    if (r->cfg.splits > 0) return r->cfg.splits;
+    int waves = r->threads / 64;
+    int want_groups = 4 * r->num_cu;
+    int s = 1;
+    if ((int)B < 2 * r->num_cu) s = (want_groups + (int)B - 1) / (int)B;
+    int max_s = std::max(1, (int)(min_clusters / (uint32_t)(4 * waves)));   // >= 4 clusters per wave
+    return std::max(1, std::min(s, max_s));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bps_last_error(const bps_renderer* r) { return r ? r->error.c_str() : g_create_error.c_str(); }
+
+bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
+    if (!cfg || !out) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: null argument");
+    *out = nullptr;
+    if (cfg->max_batch < 1) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: max_batch must be >= 1");
+    if (cfg->height < 8 || cfg->height > 128 || cfg->height % 8 || cfg->width < 8 || cfg->width > 128 || cfg->width % 8)
+        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: height and width must be multiples of 8 in 8..128");
+    if (cfg->mode != BPS_MODE_DEPTH && cfg->mode != BPS_MODE_RGBD)
+        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown mode %d", cfg->mode);
+    if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 512 && cfg->threads != 1024)
+        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 512 or 1024");
+    if (cfg->splits < 0) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be >= 0");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
+        return fail(nullptr, BPS_ERR_HIP, "bps_create: no HIP device available (this library has no CPU path)");
+    if (cfg->device < 0 || cfg->device >= ndev)
+        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: device %d out of range (0..%d)", cfg->device, ndev - 1);
+
+    bps_renderer* r = new (std::nothrow) bps_renderer();
+    if (!r) return fail(nullptr, BPS_ERR_OOM, "bps_create: out of host memory");
+    r->cfg = *cfg;
+    r->device = cfg->device;
+    bps_status st = BPS_OK;
+    auto bail = [&](bps_status code) {
+        g_create_error = r->error;
+        bps_destroy(r);
+        return code;
+    };
+    auto step = [&]() -> bps_status {
+        BPS_HIP(r, hipSetDevice(r->device));
+        hipDeviceProp_t prop;
+        BPS_HIP(r, hipGetDeviceProperties(&prop, r->device));
+        r->num_cu = prop.multiProcessorCount;
+        int lds_optin = 0;
+        if (hipDeviceGetAttribute(&lds_optin, hipDeviceAttributeSharedMemPerBlockOptin, r->device) != hipSuccess) lds_optin = 0;
+        (void)hipGetLastError();
+        r->max_lds = std::max<size_t>(prop.sharedMemPerBlock, (size_t)std::max(lds_optin, 0));
+        // largest work-group whose LDS footprint fits
+        const int order[3] = {512, 256, 1024};
+        r->threads = 0;
+        if (cfg->threads) {
+            if (bps::lds_bytes(cfg->height, cfg->width, cfg->threads) <= r->max_lds) r->threads = cfg->threads;
+        } else {
+            for (int t : order)
+                if (bps::lds_bytes(cfg->height, cfg->width, t) <= r->max_lds) { r->threads = t; break; }
+        }
+        if (!r->threads)
+            return fail(r, BPS_ERR_UNSUPPORTED, "bps_create: a %dx%d frame needs %zu bytes of LDS, device offers %zu",
+                        cfg->height, cfg->width, bps::lds_bytes(cfg->height, cfg->width, cfg->threads ? cfg->threads : 256),
+                        r->max_lds);
+        r->lds = bps::lds_bytes(cfg->height, cfg->width, r->threads);
+        BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
+        BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
+        BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
+        BPS_HIP(r, hipEventCreate(&r->ev0));
+        BPS_HIP(r, hipEventCreate(&r->ev1));
+        for (RingSlot& s : r->ring) BPS_HIP(r, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+        return BPS_OK;
+    };
+    st = step();
+    if (st != BPS_OK) return bail(st);
+    *out = r;
+    return BPS_OK;
+}
+
+void bps_destroy(bps_renderer* r) {
+    if (!r) return;
+    (void)hipSetDevice(r->device);
+    (void)hipDeviceSynchronize();
+    for (HostScene& s : r->scenes) free_scene(s);
+    for (RingSlot& s : r->ring) {
+        if (s.host) (void)hipHostFree(s.host);
+        if (s.dev) (void)hipFree(s.dev);
+        if (s.done) (void)hipEventDestroy(s.done);
+    }
+    if (r->gvis) (void)hipFree(r->gvis);
+    if (r->d_scenes) (void)hipFree(r->d_scenes);
+    if (r->ev0) (void)hipEventDestroy(r->ev0);
+    if (r->ev1) (void)hipEventDestroy(r->ev1);
+    delete r;
+}
+
+bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
+                          const uint8_t* colors, bps_scene* out_handle) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    if (!vertices || !indices || !out_handle) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: null argument");
+    if (V == 0 || T == 0) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: empty mesh (V=%u, T=%u)", V, T);
+    for (size_t i = 0; i < 3 * (size_t)T; ++i)
+        if (indices[i] >= V)
+            return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: index %u of triangle %zu is >= V=%u", indices[i], i / 3, V);
+    for (size_t i = 0; i < 3 * (size_t)V; ++i)
+        if (!std::isfinite(vertices[i]))
+            return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: vertex %zu has a non-finite coordinate", i / 3);
+    int slot = -1;
+    for (size_t i = 0; i < r->scenes.size(); ++i)
+        if (!r->scenes[i].live) { slot = (int)i; break; }
+    if (slot < 0) {
+        if ((int)r->scenes.size() >= kMaxScenes) return fail(r, BPS_ERR_OOM, "bps_load_scene: scene table full (%d)", kMaxScenes);
+        slot = (int)r->scenes.size();
+        r->scenes.emplace_back();
+    }
+    bps::ClusterSet cs;
+    try {
+        cs = bps::build_clusters(vertices, V, indices, T);
+    } catch (const std::bad_alloc&) {
+        return fail(r, BPS_ERR_OOM, "bps_load_scene: out of host memory while clustering");
+    }
+    if (cs.count == 0 || cs.count >= (1u << 25)) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: unsupported cluster count %u", cs.count);
+
+    BPS_HIP(r, hipSetDevice(r->device));
+    HostScene hs;
+    auto upload = [&](int k, const void* src, size_t bytes, const void** dst) -> bps_status {
+        BPS_HIP(r, hipMalloc(&hs.allocs[k], bytes));
+        BPS_HIP(r, hipMemcpy(hs.allocs[k], src, bytes, hipMemcpyHostToDevice));
+        *dst = hs.allocs[k];
+        hs.bytes += bytes;
+        return BPS_OK;
+    };
+    bps_status st;
+    const void* p = nullptr;
+    if ((st = upload(0, cs.verts.data(), cs.verts.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
+    hs.dev.cverts = (const float*)p;
+    if ((st = upload(1, cs.tris.data(), cs.tris.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
+    hs.dev.ctris = (const uint32_t*)p;
+    if ((st = upload(2, cs.tri_id.data(), cs.tri_id.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
+    hs.dev.ctri_id = (const uint32_t*)p;
+    if ((st = upload(3, vertices, (size_t)V * 12, &p)) != BPS_OK) { free_scene(hs); return st; }
+    hs.dev.verts = (const float*)p;
+    if ((st = upload(4, indices, (size_t)T * 12, &p)) != BPS_OK) { free_scene(hs); return st; }
+    hs.dev.indices = (const uint32_t*)p;
+    if (colors) {
+        if ((st = upload(5, colors, (size_t)V * 3, &p)) != BPS_OK) { free_scene(hs); return st; }
+        hs.dev.colors = (const uint8_t*)p;
+        hs.has_colors = true;
+    }
+    hs.dev.n_clusters = cs.count;
+    hs.dev.n_tris = T;
+    hs.dev.n_verts = V;
+    hs.dev.live = 1;
+    hs.live = true;
+    hipError_t e = hipMemcpy(r->d_scenes + slot, &hs.dev, sizeof(bps::SceneDev), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { free_scene(hs); return fail(r, BPS_ERR_HIP, "bps_load_scene: scene table update: %s", hipGetErrorString(e)); }
+    r->scenes[slot] = hs;
+    r->plan_ids.clear();
+    *out_handle = slot;
+    return BPS_OK;
+}
+
+bps_status bps_unload_scene(bps_renderer* r, bps_scene scene) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
+        return fail(r, BPS_ERR_BAD_HANDLE, "bps_unload_scene: scene %d is not loaded", scene);
+    BPS_HIP(r, hipSetDevice(r->device));
+    BPS_HIP(r, hipDeviceSynchronize());
+    free_scene(r->scenes[scene]);
+    bps::SceneDev zero{};
+    BPS_HIP(r, hipMemcpy(r->d_scenes + scene, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    r->plan_ids.clear();
+    return BPS_OK;
+}
+
+bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* view_proj, uint32_t B, float* out_depth,
+                      uint8_t* out_rgb, uint32_t* out_tri_id, void* stream_) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    if (B == 0) return BPS_OK;
+    if (!scene_ids || !view_proj || !out_depth) return fail(r, BPS_ERR_INVALID_ARG, "bps_render: null argument");
+    if (B > (uint32_t)r->cfg.max_batch)
+        return fail(r, BPS_ERR_INVALID_ARG, "bps_render: B=%u exceeds max_batch=%d", B, r->cfg.max_batch);
+    if (r->cfg.mode == BPS_MODE_RGBD)
+        return fail(r, BPS_ERR_UNSUPPORTED, "bps_render: RGB-D output is not implemented yet");
+    (void)out_rgb;
+    hipStream_t stream = (hipStream_t)stream_;
+    uint32_t min_clusters = 0xFFFFFFFFu;
+    for (uint32_t b = 0; b < B; ++b) {
+        bps_scene s = scene_ids[b];
+        if (s < 0 || (size_t)s >= r->scenes.size() || !r->scenes[s].live)
+            return fail(r, BPS_ERR_BAD_HANDLE, "bps_render: scene_ids[%u]=%d is not a loaded scene", b, s);
+        min_clusters = std::min(min_clusters, r->scenes[s].dev.n_clusters);
+    }
+    BPS_HIP(r, hipSetDevice(r->device));
+    const int H = r->cfg.height, W = r->cfg.width;
+    const size_t HW = (size_t)H * W;
+    const int S = plan_splits(r, B, min_clusters);
+
+    // ---- plan: one work item per (environment, slice of its scene's clusters); environments of
+    // one scene are kept on one accelerator die so its L2 serves every re-read of that scene
+    bool replan = r->plan_splits != S || r->plan_ids.size() != B || std::memcmp(r->plan_ids.data(), scene_ids, B * sizeof(bps_scene)) != 0;
+    if (replan) {
+        std::vector<uint32_t> order(B);
+        for (uint32_t b = 0; b < B; ++b) order[b] = b;
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return scene_ids[a] < scene_ids[b]; });
+        std::vector<bps::WorkItem> sorted;
+        sorted.reserve((size_t)B * S);
+        for (uint32_t k = 0; k < B; ++k) {
+            uint32_t b = order[k];
+            uint32_t C = r->scenes[scene_ids[b]].dev.n_clusters;
+            for (int s = 0; s < S; ++s) {
+                bps::WorkItem it;
+                it.env = b;
+                it.scene = (uint32_t)scene_ids[b];
+                it.c_begin = (uint32_t)((uint64_t)C * s / S);
+                it.c_end = (uint32_t)((uint64_t)C * (s + 1) / S);
+                sorted.push_back(it);
+            }
+        }
+        const size_t n = sorted.size();
+        r->plan_items.resize(n);
+        // block i runs on die i % 8: give die x the x-th contiguous chunk of the sorted list
+        size_t start = 0;
+        for (int x = 0; x < kXcds; ++x) {
+            size_t cnt = n / kXcds + ((size_t)x < n % kXcds ? 1 : 0);
+            for (size_t k = 0; k < cnt; ++k) r->plan_items[x + k * kXcds] = sorted[start + k];
+            start += cnt;
+        }
+        r->plan_ids.assign(scene_ids, scene_ids + B);
+        r->plan_splits = S;
+    }
+    const size_t n_items = r->plan_items.size();
+
+    // ---- stage the request (work items + matrices unless they already live on the device)
+    hipPointerAttribute_t attr;
+    bool vp_on_device = false;
+    if (hipPointerGetAttributes(&attr, view_proj) == hipSuccess) vp_on_device = attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged;
+    (void)hipGetLastError();
+    const size_t items_bytes = n_items * sizeof(bps::WorkItem);
+    const size_t vp_bytes = (size_t)B * 16 * sizeof(float);
+    const size_t need = items_bytes + vp_bytes;
+    RingSlot& slot = r->ring[r->ring_next];
+    r->ring_next = (r->ring_next + 1) % kRing;
+    if (slot.pending) {
+        BPS_HIP(r, hipEventSynchronize(slot.done));
+        slot.pending = false;
+    }
+    if (slot.capacity < need) {
+        if (slot.host) (void)hipHostFree(slot.host);
+        if (slot.dev) (void)hipFree(slot.dev);
+        slot.host = slot.dev = nullptr;
+        slot.capacity = 0;
+        size_t cap = std::max<size_t>(need, 1 << 16);
+        BPS_HIP(r, hipHostMalloc((void**)&slot.host, cap, hipHostMallocDefault));
+        BPS_HIP(r, hipMalloc((void**)&slot.dev, cap));
+        slot.capacity = cap;
+    }
+    std::memcpy(slot.host, r->plan_items.data(), items_bytes);
+    size_t copy_bytes = items_bytes;
+    if (!vp_on_device) {
+        std::memcpy(slot.host + items_bytes, view_proj, vp_bytes);
+        copy_bytes += vp_bytes;
+    }
+    BPS_HIP(r, hipMemcpyAsync(slot.dev, slot.host, copy_bytes, hipMemcpyHostToDevice, stream));
+    const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(slot.dev);
+    const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(slot.dev + items_bytes);
+
+    // ---- global visibility buffer, only when frames are split
+    if (S > 1 && !r->gvis) {
+        size_t n = (size_t)r->cfg.max_batch * HW;
+        BPS_HIP(r, hipMalloc((void**)&r->gvis, n * sizeof(unsigned long long)));
+        hipLaunchKernelGGL(bps::k_fill_keys, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, r->gvis, n);
+        BPS_HIP(r, hipGetLastError());
+    }
+
+    bps::FrameParams fp;
+    fp.H = H;
+    fp.W = W;
+    fp.sx = 128.0f * (float)W;
+    fp.sy = 128.0f * (float)H;
+    fp.xmax = 2.0f * fp.sx + 64.0f;
+    fp.ymax = 2.0f * fp.sy + 64.0f;
+    fp.background = r->cfg.background_depth;
+    fp.merge = S > 1 ? 1 : 0;
+
+    if (r->profiling) BPS_HIP(r, hipEventRecord(r->ev0, stream));
+    bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, d_items, d_vp, fp, r->gvis, out_depth,
+                       out_tri_id);
+    BPS_HIP(r, hipGetLastError());
+    if (S > 1) {
+        size_t n = (size_t)B * HW;
+        hipLaunchKernelGGL(bps::k_resolve, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, r->gvis, n, fp.background,
+                           out_depth, out_tri_id);
+        BPS_HIP(r, hipGetLastError());
+    }
+    if (r->profiling) {
+        BPS_HIP(r, hipEventRecord(r->ev1, stream));
+        r->timed = true;
+    }
+    BPS_HIP(r, hipEventRecord(slot.done, stream));
+    slot.pending = true;
+    r->last_splits = (uint64_t)S;
+    r->last_groups = (uint64_t)n_items;
+    return BPS_OK;
+}
+
+bps_status bps_set_profiling(bps_renderer* r, int32_t enable) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    r->profiling = enable != 0;
+    r->timed = false;
+    return BPS_OK;
+}
+
+bps_status bps_last_kernel_ms(bps_renderer* r, float* ms) {
+    if (!r || !ms) return BPS_ERR_INVALID_ARG;
+    if (!r->timed) return fail(r, BPS_ERR_INVALID_ARG, "bps_last_kernel_ms: no profiled request yet");
+    BPS_HIP(r, hipEventSynchronize(r->ev1));
+    BPS_HIP(r, hipEventElapsedTime(ms, r->ev0, r->ev1));
+    return BPS_OK;
+}
+
+bps_status bps_query(bps_renderer* r, bps_scene scene, int32_t what, uint64_t* value) {
+    if (!r || !value) return BPS_ERR_INVALID_ARG;
+    if (what >= 0 && what <= 3) {
+        if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
+            return fail(r, BPS_ERR_BAD_HANDLE, "bps_query: scene %d is not loaded", scene);
+        const HostScene& s = r->scenes[scene];
+        *value = what == 0 ? s.dev.n_clusters : what == 1 ? s.dev.n_tris : what == 2 ? s.dev.n_verts : s.bytes;
+        return BPS_OK;
+    }
+    switch (what) {
+    case 4: *value = r->last_splits; return BPS_OK;
+    case 5: *value = r->last_groups; return BPS_OK;
+    case 6: *value = (uint64_t)r->threads; return BPS_OK;
+    case 7: *value = (uint64_t)r->lds; return BPS_OK;
+    default: return fail(r, BPS_ERR_INVALID_ARG, "bps_query: unknown item %d", what);
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Device side of the batch renderer: one fused geometry + rasterisation kernel and a resolve
+// kernel, written for gfx950 (64-lane wavefronts, 160 KB LDS per CU).
+//
+// One work-group renders (a slice of) one environment's frame (paper Sec. 3.2: every
+// environment of the batch is drawn in a single request).  The frame's visibility buffer --
+// H*W packed keys (depth bits << 32 | triangle id) -- lives in LDS for the whole kernel, so the
+// z-test is a 64-bit LDS atomic min and the frame is written to HBM exactly once.  Each wavefront
+// streams clusters of <= 64 vertices / <= 128 triangles:
+//   vertex phase   one lane per vertex: clip = M v, six-plane outcodes, projection, 1/256-px snap
+//   cluster cull   all 64 vertices outside one plane (wave ballot)  -> next cluster
+//   triangle phase two triangles per lane: outcode reject, bounding box vs pixel centres
+//   compaction     survivors are appended to per-wave LDS queues with ballot + prefix count so
+//                  that the expensive steps run on full wavefronts:
+//                    small queue  triangles touching <= 4 pixel centres, one lane per triangle
+//                    clip queue   triangles straddling a frustum plane, one lane per triangle
+//                  large triangles are rasterised by the whole wavefront, 8x8 pixels at a time.
+// All float arithmetic follows one fixed IEEE sequence (explicit fmaf, no contraction, exact
+// division) so that coverage and ids are reproducible bit for bit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bps {
+
+struct SceneDev {
+    const float* cverts;       // [C][3][64] cluster vertex positions, x then y then z
+    const uint32_t* ctris;     // [C][128]   packed local indices, count in bits 24..31 of word 0
+    const uint32_t* ctri_id;   // [C][128]   original triangle row
+    const float* verts;        // [V][3]     original arrays, used when shading
+    const uint32_t* indices;   // [T][3]
+    const uint8_t* colors;     // [V][3] or null
+    uint32_t n_clusters, n_tris, n_verts, live;
+};
+
+struct WorkItem {
+    uint32_t env, scene, c_begin, c_end;
+};
+
+struct FrameParams {
+    int32_t H, W;
+    float sx, sy;          // 128*W, 128*H
+    float xmax, ymax;      // 2*sx + 64, 2*sy + 64
+    float background;
+    int32_t merge;         // 0: resolve straight to the output; 1: atomic-min into the global buffer
+};
+
+constexpr unsigned long long kEmptyKey = ~0ull;
+constexpr int kBias = 64;              // packed screen coordinates are stored + 64
+constexpr int kSmallMax = 4;           // pixel centres a "small" triangle may touch
+constexpr uint32_t kInvalid = 0x40u;   // outcode bit: vertex unusable, drop its triangles
+
+// per-wave LDS block: 64 staged vertices (16 B each), small queue 8 x 64 words, clip queue 192 words
+constexpr uint32_t kWaveLdsBytes = 64 * 16 + 8 * 64 * 4 + 192 * 4;
+
+__host__ __device__ inline size_t lds_bytes(int H, int W, int threads) {
+    return (size_t)H * W * 8 + (size_t)(threads / 64) * kWaveLdsBytes;
+}
+
+template <int NT>
+__global__ void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
+                         const float* __restrict__ view_proj, FrameParams fp, unsigned long long* __restrict__ gvis,
+                         float* __restrict__ out_depth, uint32_t* __restrict__ out_id);
+
+__global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float background,
+                          float* __restrict__ out_depth, uint32_t* __restrict__ out_id);
+
+__global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n);
+
+void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
+                   const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
+                   uint32_t* out_id);
+hipError_t prepare_raster(int threads, size_t lds);
+
+}  // namespace bps

@@ -1,0 +1,84 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+NOHIT = 0xFFFFFFFF
+
+
+def _render_gpu(scenes, scene_ids, view_proj, H, W, splits=0, threads=0, background=0.0, device_matrices=False):
+    import torch
+    import paper_2103_07013_amd as bps
+    B = len(scene_ids)
+    with bps.Renderer(max_batch=B, height=H, width=W, splits=splits, threads=threads,
+                      background_depth=background) as r:
+        handles = [r.load_scene(s.vertices, s.indices, s.colors) for s in scenes]
+        ids = np.array([handles[k] for k in scene_ids], np.int32)
+        vp = torch.from_numpy(np.ascontiguousarray(view_proj)).cuda() if device_matrices else view_proj
+        depth, _, tid = r.render(ids, vp, want_tri_id=True)
+        torch.cuda.synchronize()
+        info = dict(splits=bps.bps_query(r.handle, 0, 4), groups=bps.bps_query(r.handle, 0, 5),
+                    threads=bps.bps_query(r.handle, 0, 6), lds=bps.bps_query(r.handle, 0, 7))
+        return depth.cpu().numpy(), tid.cpu().numpy().view(np.uint32), info
+
+
+def _compare(gd, gi, ref, tag=""):
+    od, oi = ref["depth"], ref["tri_id"]
+    bad_id = gi != oi
+    assert not bad_id.any(), f"{tag}: {int(bad_id.sum())} pixels differ in coverage / triangle id, first at {np.argwhere(bad_id)[:5]}"
+    # bar: 1e-5 relative; the arithmetic is the same IEEE sequence so exact equality is expected
+    rel = np.abs(gd - od) <= 1e-5 * np.abs(od)
+    assert rel.all(), f"{tag}: depth off at {np.argwhere(~rel)[:5]}"
+    return int((gd != od).sum())
+
+
+def _oracle(w):
+    import oracle
+    return oracle.render_batch(w.scenes, w.scene_ids, w.view_proj, w.H, w.W)
+
+
+@pytest.mark.parametrize("splits,threads", [(1, 512), (0, 0), (3, 256), (2, 1024)])
+def test_config1_room_matches_oracle(splits, threads):
+    w = synth.build_config(1)
+    ref = _oracle(w)
+    gd, gi, info = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, splits=splits, threads=threads)
+    print(info)
+    nd = _compare(gd, gi, ref, f"config1 splits={splits} threads={threads}")
+    assert nd == 0, f"{nd} depths differ in the last bits"
+    assert (gi == NOHIT).sum() == 0          # closed room: no background
+
+
+def test_config2_slice_matches_oracle():
+    w = synth.build_config(2, B=24)
+    ref = _oracle(w)
+    for splits in (1, 5):
+        gd, gi, info = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, splits=splits)
+        _compare(gd, gi, ref, f"config2 splits={splits}")
+
+
+def test_mixed_scenes_interleaved_ids():
+    w = synth.build_config(3, B=16, scale=0.1)       # 4 scenes x ~50k triangles, ids b mod 4
+    ref = _oracle(w)
+    gd, gi, _ = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, device_matrices=True)
+    _compare(gd, gi, ref, "mixed")
+
+
+def test_random_soup_with_heavy_clipping():
+    import oracle
+    rng = np.random.default_rng(7)
+    n = 3000
+    c = np.stack([rng.uniform(-4, 4, n), rng.uniform(-4, 4, n), rng.uniform(-9, 2, n)], 1)
+    v = (c[:, None, :] + rng.uniform(-1.5, 1.5, (n, 3, 3))).reshape(-1, 3).astype(np.float32)
+    idx = np.arange(3 * n, dtype=np.uint32).reshape(n, 3)
+    scene = synth.Scene(v, idx, np.zeros((3 * n, 3), np.uint8), (1, 1))
+    Ms = np.stack([synth.view_proj_from_pose((0.1 * k, -0.2, 0.5), 0.4 * k, 0.15 * (k - 3), near=0.05, far=12.0)
+                   for k in range(8)])
+    for (H, W) in ((64, 64), (32, 96), (128, 128)):
+        Ma = np.stack([synth.view_proj_from_pose((0.1 * k, -0.2, 0.5), 0.4 * k, 0.15 * (k - 3), near=0.05, far=12.0,
+                                                 aspect=W / H) for k in range(8)])
+        ref = oracle.render_scene(v, idx, Ma, H, W)
+        gd, gi, _ = _render_gpu([scene], [0] * 8, Ma, H, W, background=3.5)
+        ref["depth"][ref["tri_id"] == NOHIT] = 3.5
+        _compare(gd, gi, ref, f"soup {H}x{W}")
