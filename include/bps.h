@@ -75,8 +75,8 @@ bps_status bps_load_scene(bps_renderer *r, const float *vertices, uint32_t V, co
 /* Frees a scene.  The caller must not unload a scene that queued renders still use. */
 bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 
-/* One batched render request (Sec. 3: "the renderer processes the batch of environment states
- * by simultaneously rendering N frames and exposing the result directly in GPU memory").
+/* One batched render request (Sec. 3: the whole batch of N environment states is rendered at
+ * once and the N frames are left in GPU memory for the consumer).
  *   scene_ids   host   int32 [B]          scene of each environment
  *   view_proj   host or device float32 [B][4][4], row-major
  *   out_depth   DEVICE float32 [B][H][W]  eye depth, background_depth where nothing is hit
@@ -88,11 +88,15 @@ bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
                       float *out_depth, uint8_t *out_rgb, uint32_t *out_tri_id, void *stream);
 
-/* Timing aid for benchmarks: when enabled, bps_render brackets its rasterisation kernel with
- * HIP events on the caller's stream.  bps_last_kernel_ms waits for those events and returns the
- * kernel's duration in milliseconds for the most recent request. */
+/* Timing aid for benchmarks: when enabled, bps_render brackets its rasterisation kernel(s) with
+ * HIP events on the caller's stream (request staging is outside the bracket).
+ * bps_last_kernel_ms waits for the most recent request's events and returns its duration in
+ * milliseconds.  bps_kernel_ms_total waits for every request profiled since the last call (or
+ * since profiling was enabled; at most 4096 are remembered), returns their count and summed
+ * duration, and forgets them. */
 bps_status bps_set_profiling(bps_renderer *r, int32_t enable);
 bps_status bps_last_kernel_ms(bps_renderer *r, float *ms);
+bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total_ms);
 
 /* Facts about a loaded scene and the launch plan, for benchmarks and tests.
  * what: 0 = clusters in the scene, 1 = triangles, 2 = vertices, 3 = device bytes held,

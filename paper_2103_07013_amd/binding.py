@@ -10,7 +10,7 @@ from . import build as _build
 
 MODE_DEPTH, MODE_RGBD = 0, 1
 EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_unload_scene", "bps_render", "bps_set_profiling",
-           "bps_last_kernel_ms", "bps_query", "bps_last_error"]
+           "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_query", "bps_last_error"]
 
 
 class BpsError(RuntimeError):
@@ -51,6 +51,8 @@ def load_library():
     lib.bps_set_profiling.argtypes = [vp, ctypes.c_int32]
     lib.bps_last_kernel_ms.restype = ctypes.c_int32
     lib.bps_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.bps_kernel_ms_total.restype = ctypes.c_int32
+    lib.bps_kernel_ms_total.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_float)]
     lib.bps_query.restype = ctypes.c_int32
     lib.bps_query.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_uint64)]
     lib.bps_last_error.restype = ctypes.c_char_p
@@ -144,6 +146,13 @@ def bps_last_kernel_ms(handle):
     ms = ctypes.c_float(0.0)
     _check(load_library().bps_last_kernel_ms(handle, ctypes.byref(ms)), handle)
     return float(ms.value)
+
+
+def bps_kernel_ms_total(handle):
+    """(launches, total_ms) of every request profiled since the previous call."""
+    n, ms = ctypes.c_uint32(0), ctypes.c_float(0.0)
+    _check(load_library().bps_kernel_ms_total(handle, ctypes.byref(n), ctypes.byref(ms)), handle)
+    return int(n.value), float(ms.value)
 
 
 def bps_query(handle, scene, what):

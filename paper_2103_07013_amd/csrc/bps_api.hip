@@ -20,6 +20,7 @@ namespace {
 constexpr int kMaxScenes = 4096;
 constexpr int kRing = 4;          // request staging slots in flight
 constexpr int kXcds = 8;          // work-groups are dealt round-robin to 8 accelerator dies
+constexpr size_t kMaxProfiled = 4096;   // profiled requests remembered between two reads of the totals
 
 thread_local std::string g_create_error = "";
 
@@ -54,8 +55,9 @@ struct bps_renderer {
     RingSlot ring[kRing];
     int ring_next = 0;
     unsigned long long* gvis = nullptr;   // [max_batch][H][W], only for split frames
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    bool profiling = false, timed = false;
+    std::vector<hipEvent_t> ev;           // profiling: pairs (start, stop), one pair per request
+    size_t ev_used = 0;
+    bool profiling = false;
     // cached plan: valid while the scene ids and split count repeat
     std::vector<bps_scene> plan_ids;
     int plan_splits = 0;
@@ -162,8 +164,6 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
         BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
-        BPS_HIP(r, hipEventCreate(&r->ev0));
-        BPS_HIP(r, hipEventCreate(&r->ev1));
         for (RingSlot& s : r->ring) BPS_HIP(r, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
         return BPS_OK;
     };
@@ -185,8 +185,7 @@ void bps_destroy(bps_renderer* r) {
     }
     if (r->gvis) (void)hipFree(r->gvis);
     if (r->d_scenes) (void)hipFree(r->d_scenes);
-    if (r->ev0) (void)hipEventDestroy(r->ev0);
-    if (r->ev1) (void)hipEventDestroy(r->ev1);
+    for (hipEvent_t e : r->ev) (void)hipEventDestroy(e);
     delete r;
 }
 
@@ -379,7 +378,17 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     fp.background = r->cfg.background_depth;
     fp.merge = S > 1 ? 1 : 0;
 
-    if (r->profiling) BPS_HIP(r, hipEventRecord(r->ev0, stream));
+    hipEvent_t ev_stop = nullptr;
+    if (r->profiling && r->ev_used + 2 <= 2 * kMaxProfiled) {
+        while (r->ev.size() < r->ev_used + 2) {
+            hipEvent_t e;
+            BPS_HIP(r, hipEventCreate(&e));
+            r->ev.push_back(e);
+        }
+        BPS_HIP(r, hipEventRecord(r->ev[r->ev_used], stream));
+        ev_stop = r->ev[r->ev_used + 1];
+        r->ev_used += 2;
+    }
     bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, d_items, d_vp, fp, r->gvis, out_depth,
                        out_tri_id);
     BPS_HIP(r, hipGetLastError());
@@ -389,10 +398,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
                            out_depth, out_tri_id);
         BPS_HIP(r, hipGetLastError());
     }
-    if (r->profiling) {
-        BPS_HIP(r, hipEventRecord(r->ev1, stream));
-        r->timed = true;
-    }
+    if (ev_stop) BPS_HIP(r, hipEventRecord(ev_stop, stream));
     BPS_HIP(r, hipEventRecord(slot.done, stream));
     slot.pending = true;
     r->last_splits = (uint64_t)S;
@@ -403,15 +409,30 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
 bps_status bps_set_profiling(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
     r->profiling = enable != 0;
-    r->timed = false;
+    r->ev_used = 0;
     return BPS_OK;
 }
 
 bps_status bps_last_kernel_ms(bps_renderer* r, float* ms) {
     if (!r || !ms) return BPS_ERR_INVALID_ARG;
-    if (!r->timed) return fail(r, BPS_ERR_INVALID_ARG, "bps_last_kernel_ms: no profiled request yet");
-    BPS_HIP(r, hipEventSynchronize(r->ev1));
-    BPS_HIP(r, hipEventElapsedTime(ms, r->ev0, r->ev1));
+    if (r->ev_used < 2) return fail(r, BPS_ERR_INVALID_ARG, "bps_last_kernel_ms: no profiled request yet");
+    BPS_HIP(r, hipEventSynchronize(r->ev[r->ev_used - 1]));
+    BPS_HIP(r, hipEventElapsedTime(ms, r->ev[r->ev_used - 2], r->ev[r->ev_used - 1]));
+    return BPS_OK;
+}
+
+bps_status bps_kernel_ms_total(bps_renderer* r, uint32_t* launches, float* total_ms) {
+    if (!r || !launches || !total_ms) return BPS_ERR_INVALID_ARG;
+    float sum = 0.0f;
+    for (size_t k = 0; k + 1 < r->ev_used; k += 2) {
+        float ms = 0.0f;
+        BPS_HIP(r, hipEventSynchronize(r->ev[k + 1]));
+        BPS_HIP(r, hipEventElapsedTime(&ms, r->ev[k], r->ev[k + 1]));
+        sum += ms;
+    }
+    *launches = (uint32_t)(r->ev_used / 2);
+    *total_ms = sum;
+    r->ev_used = 0;
     return BPS_OK;
 }
 
