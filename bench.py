@@ -52,7 +52,22 @@ def main():
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--cpu-envs", type=int, default=512, help="environments in the oracle timing sample (0 = skip)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of rendering, run a plain device-to-device copy of this many MiB five times "
+                         "(reference reading for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.copy_calibration > 0:
+        import torch
+        n = args.copy_calibration * (1 << 20)
+        a = torch.full((n // 4,), 1.0, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_MiB": args.copy_calibration, "reads_MiB": args.copy_calibration,
+                          "writes_MiB": args.copy_calibration, "repeats": 5}))
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build renders on ONE GPU; frames shard by environment with no exchange, "
                  "so run one process per GPU instead of --gpus %d" % args.gpus)
