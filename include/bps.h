@@ -72,6 +72,15 @@ void bps_destroy(bps_renderer *r);
 bps_status bps_load_scene(bps_renderer *r, const float *vertices, uint32_t V, const uint32_t *indices, uint32_t T,
                           const uint8_t *colors, bps_scene *out_handle);
 
+/* Host-only helper (no GPU needed): re-pack a mesh exactly as bps_load_scene does and copy the
+ * cluster arrays out, for tests and tools.  On entry *count is the capacity of the output
+ * arrays in clusters (ignored when all three are NULL); on return it is the cluster count.
+ *   verts_out [count][3][64] float32   x, y, z planes; unused lanes repeat the first vertex
+ *   tris_out  [count][128]   uint32    i0 | i1 << 8 | i2 << 16, used-slot count in bits 24..31 of word 0
+ *   ids_out   [count][128]   uint32    row in `indices`, 0xFFFFFFFF for unused slots */
+bps_status bps_pack_clusters(const float *vertices, uint32_t V, const uint32_t *indices, uint32_t T, uint32_t *count,
+                             float *verts_out, uint32_t *tris_out, uint32_t *ids_out);
+
 /* Frees a scene.  The caller must not unload a scene that queued renders still use. */
 bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 

@@ -9,7 +9,7 @@ import numpy as np
 from . import build as _build
 
 MODE_DEPTH, MODE_RGBD = 0, 1
-EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_unload_scene", "bps_render", "bps_set_profiling",
+EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
            "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_query", "bps_last_error"]
 
 
@@ -43,6 +43,8 @@ def load_library():
     lib.bps_destroy.argtypes = [vp]
     lib.bps_load_scene.restype = ctypes.c_int32
     lib.bps_load_scene.argtypes = [vp, vp, ctypes.c_uint32, vp, ctypes.c_uint32, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.bps_pack_clusters.restype = ctypes.c_int32
+    lib.bps_pack_clusters.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32), vp, vp, vp]
     lib.bps_unload_scene.restype = ctypes.c_int32
     lib.bps_unload_scene.argtypes = [vp, ctypes.c_int32]
     lib.bps_render.restype = ctypes.c_int32
@@ -95,6 +97,26 @@ def bps_load_scene(handle, vertices, indices, colors=None):
     _check(lib.bps_load_scene(handle, v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0],
                               None if c is None else c.ctypes.data, ctypes.byref(out)), handle)
     return int(out.value)
+
+
+def bps_pack_clusters(vertices, indices):
+    """Host-only: (verts [C,3,64] f32, tris [C,128] u32, ids [C,128] u32) as bps_load_scene would upload."""
+    lib = load_library()
+    v = np.ascontiguousarray(vertices, np.float32).reshape(-1, 3)
+    i = np.ascontiguousarray(indices, np.uint32).reshape(-1, 3)
+    n = ctypes.c_uint32(0)
+    st = lib.bps_pack_clusters(v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0], ctypes.byref(n), None, None, None)
+    if st != 0:
+        raise BpsError(st, "bps_pack_clusters rejected the mesh")
+    C = int(n.value)
+    verts = np.empty((C, 3, 64), np.float32)
+    tris = np.empty((C, 128), np.uint32)
+    ids = np.empty((C, 128), np.uint32)
+    st = lib.bps_pack_clusters(v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0], ctypes.byref(n),
+                               verts.ctypes.data, tris.ctypes.data, ids.ctypes.data)
+    if st != 0:
+        raise BpsError(st, "bps_pack_clusters failed")
+    return verts, tris, ids
 
 
 def bps_unload_scene(handle, scene):

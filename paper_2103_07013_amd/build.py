@@ -7,8 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbps.so")
-SOURCES = ["bps_api.hip", "raster_kernels.hip", "clusters.cpp"]
-HEADERS = ["raster_kernels.h", "clusters.h", os.path.join("..", "..", "include", "bps.h")]
+SOURCES = ["bps_api.hip", "raster_kernels.hip", "shade_kernels.hip", "clusters.cpp"]
+HEADERS = ["raster_kernels.h", "raster_device.h", "clusters.h", os.path.join("..", "..", "include", "bps.h")]
 # -ffp-contract=off: the numeric rule fixes where fused multiply-adds happen.
 # packed FP32 instructions are switched off on purpose (hipcc's host pass does not know the
 # feature and says so; that message is harmless).

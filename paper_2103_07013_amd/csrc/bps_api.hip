@@ -55,6 +55,7 @@ struct bps_renderer {
     RingSlot ring[kRing];
     int ring_next = 0;
     unsigned long long* gvis = nullptr;   // [max_batch][H][W], only for split frames
+    uint32_t* ids = nullptr;              // [max_batch][H][W], RGB-D requests without a caller id buffer
     std::vector<hipEvent_t> ev;           // profiling: pairs (start, stop), one pair per request
     size_t ev_used = 0;
     bool profiling = false;
@@ -184,6 +185,7 @@ void bps_destroy(bps_renderer* r) {
         if (s.done) (void)hipEventDestroy(s.done);
     }
     if (r->gvis) (void)hipFree(r->gvis);
+    if (r->ids) (void)hipFree(r->ids);
     if (r->d_scenes) (void)hipFree(r->d_scenes);
     for (hipEvent_t e : r->ev) (void)hipEventDestroy(e);
     delete r;
@@ -255,6 +257,27 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
     return BPS_OK;
 }
 
+bps_status bps_pack_clusters(const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T, uint32_t* count,
+                             float* verts_out, uint32_t* tris_out, uint32_t* ids_out) {
+    if (!vertices || !indices || !count || V == 0 || T == 0) return BPS_ERR_INVALID_ARG;
+    for (size_t i = 0; i < 3 * (size_t)T; ++i)
+        if (indices[i] >= V) return BPS_ERR_INVALID_ARG;
+    bps::ClusterSet cs;
+    try {
+        cs = bps::build_clusters(vertices, V, indices, T);
+    } catch (const std::bad_alloc&) {
+        return BPS_ERR_OOM;
+    }
+    const uint32_t room = *count;
+    *count = cs.count;
+    if (!verts_out && !tris_out && !ids_out) return BPS_OK;
+    if (room < cs.count) return BPS_ERR_INVALID_ARG;
+    if (verts_out) std::memcpy(verts_out, cs.verts.data(), cs.verts.size() * sizeof(float));
+    if (tris_out) std::memcpy(tris_out, cs.tris.data(), cs.tris.size() * sizeof(uint32_t));
+    if (ids_out) std::memcpy(ids_out, cs.tri_id.data(), cs.tri_id.size() * sizeof(uint32_t));
+    return BPS_OK;
+}
+
 bps_status bps_unload_scene(bps_renderer* r, bps_scene scene) {
     if (!r) return BPS_ERR_INVALID_ARG;
     if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
@@ -275,15 +298,16 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     if (!scene_ids || !view_proj || !out_depth) return fail(r, BPS_ERR_INVALID_ARG, "bps_render: null argument");
     if (B > (uint32_t)r->cfg.max_batch)
         return fail(r, BPS_ERR_INVALID_ARG, "bps_render: B=%u exceeds max_batch=%d", B, r->cfg.max_batch);
-    if (r->cfg.mode == BPS_MODE_RGBD)
-        return fail(r, BPS_ERR_UNSUPPORTED, "bps_render: RGB-D output is not implemented yet");
-    (void)out_rgb;
+    const bool rgbd = r->cfg.mode == BPS_MODE_RGBD;
+    if (rgbd && !out_rgb) return fail(r, BPS_ERR_INVALID_ARG, "bps_render: out_rgb is required in RGB-D mode");
     hipStream_t stream = (hipStream_t)stream_;
     uint32_t min_clusters = 0xFFFFFFFFu;
     for (uint32_t b = 0; b < B; ++b) {
         bps_scene s = scene_ids[b];
         if (s < 0 || (size_t)s >= r->scenes.size() || !r->scenes[s].live)
             return fail(r, BPS_ERR_BAD_HANDLE, "bps_render: scene_ids[%u]=%d is not a loaded scene", b, s);
+        if (rgbd && !r->scenes[s].has_colors)
+            return fail(r, BPS_ERR_INVALID_ARG, "bps_render: scene %d (scene_ids[%u]) was loaded without colours", s, b);
         min_clusters = std::min(min_clusters, r->scenes[s].dev.n_clusters);
     }
     BPS_HIP(r, hipSetDevice(r->device));
@@ -333,7 +357,8 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     (void)hipGetLastError();
     const size_t items_bytes = n_items * sizeof(bps::WorkItem);
     const size_t vp_bytes = (size_t)B * 16 * sizeof(float);
-    const size_t need = items_bytes + vp_bytes;
+    const size_t ids_bytes = rgbd ? (size_t)B * sizeof(uint32_t) : 0;
+    const size_t need = items_bytes + ids_bytes + vp_bytes;
     RingSlot& slot = r->ring[r->ring_next];
     r->ring_next = (r->ring_next + 1) % kRing;
     if (slot.pending) {
@@ -351,14 +376,22 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         slot.capacity = cap;
     }
     std::memcpy(slot.host, r->plan_items.data(), items_bytes);
-    size_t copy_bytes = items_bytes;
+    if (rgbd) std::memcpy(slot.host + items_bytes, scene_ids, ids_bytes);
+    size_t copy_bytes = items_bytes + ids_bytes;
     if (!vp_on_device) {
-        std::memcpy(slot.host + items_bytes, view_proj, vp_bytes);
+        std::memcpy(slot.host + copy_bytes, view_proj, vp_bytes);
         copy_bytes += vp_bytes;
     }
     BPS_HIP(r, hipMemcpyAsync(slot.dev, slot.host, copy_bytes, hipMemcpyHostToDevice, stream));
     const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(slot.dev);
-    const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(slot.dev + items_bytes);
+    const uint32_t* d_env_scene = reinterpret_cast<const uint32_t*>(slot.dev + items_bytes);
+    const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(slot.dev + items_bytes + ids_bytes);
+
+    // ---- RGB-D: the colour pass needs the winning triangle ids even when the caller does not
+    if (rgbd && !out_tri_id) {
+        if (!r->ids) BPS_HIP(r, hipMalloc((void**)&r->ids, (size_t)r->cfg.max_batch * HW * sizeof(uint32_t)));
+        out_tri_id = r->ids;
+    }
 
     // ---- global visibility buffer, only when frames are split
     if (S > 1 && !r->gvis) {
@@ -396,6 +429,10 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         size_t n = (size_t)B * HW;
         hipLaunchKernelGGL(bps::k_resolve, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, r->gvis, n, fp.background,
                            out_depth, out_tri_id);
+        BPS_HIP(r, hipGetLastError());
+    }
+    if (rgbd) {
+        bps::launch_shade(stream, r->d_scenes, d_env_scene, d_vp, fp, B, out_tri_id, out_rgb);
         BPS_HIP(r, hipGetLastError());
     }
     if (ev_stop) BPS_HIP(r, hipEventRecord(ev_stop, stream));

@@ -70,5 +70,7 @@ void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id);
 hipError_t prepare_raster(int threads, size_t lds);
+void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
+                  const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb);
 
 }  // namespace bps

@@ -1,0 +1,157 @@
+// Colour resolve for RGB-D frames (stand-in for the paper's textured RGB sensor, Sec. 4.1):
+// per-vertex uint8 colours, perspective-correct interpolation at the pixel centre of the
+// triangle that won the z-test.  Runs after k_raster, one thread per pixel: the winner's
+// three vertices are transformed, clipped and set up again with exactly the arithmetic of
+// the raster kernel, so the barycentric weights are the ones the z-test used.
+//   cn = fma(e2/w2, c2, fma(e1/w1, c1, (e0/w0) c0)),  out = clamp(rint(cn / num), 0, 255)
+#include "raster_device.h"
+#include "raster_kernels.h"
+
+namespace bps {
+namespace {
+
+using namespace dev;
+
+struct CVert {
+    Clip4 c;
+    float r, g, b;
+};
+
+struct SVert {
+    uint32_t xy;
+    float iw, r, g, b;
+};
+
+// Colour of pixel (i, j) from one snapped fan triangle; returns false when it does not cover the pixel.
+__device__ __forceinline__ bool piece_colour(const SVert& v0, const SVert& v1, const SVert& v2, int i, int j,
+                                             float& depth, float (&rgb)[3]) {
+    Setup s = make_setup(v0.xy, v1.xy, v2.xy, v0.iw, v1.iw, v2.iw);
+    if (s.A2 == 0) return false;
+    const SVert& a = v0;
+    const SVert& b = s.swapped ? v2 : v1;
+    const SVert& c = s.swapped ? v1 : v2;
+    int px = (i << 8) + 128 + kBias, py = (j << 8) + 128 + kBias;
+    int E0 = __mul24(s.dx0, py - s.Y1) - __mul24(s.dy0, px - s.X1);
+    int E1 = __mul24(s.dx1, py - s.Y2) - __mul24(s.dy1, px - s.X2);
+    int E2 = __mul24(s.dx2, py - s.Y0) - __mul24(s.dy2, px - s.X0);
+    if (((E0 + s.b0) | (E1 + s.b1) | (E2 + s.b2)) < 0) return false;
+    float e0 = (float)E0, e1 = (float)E1, e2 = (float)E2;
+    float num = fmaf(e2, s.iw2, fmaf(e1, s.iw1, e0 * s.iw0));
+    depth = (float)s.A2 / num;
+    float w0 = e0 * s.iw0, w1 = e1 * s.iw1, w2 = e2 * s.iw2;
+    rgb[0] = fmaf(w2, c.r, fmaf(w1, b.r, w0 * a.r)) / num;
+    rgb[1] = fmaf(w2, c.g, fmaf(w1, b.g, w0 * a.g)) / num;
+    rgb[2] = fmaf(w2, c.b, fmaf(w1, b.b, w0 * a.b)) / num;
+    return true;
+}
+
+__device__ __forceinline__ uint8_t to_u8(float v) {
+    if (!(v == v)) return 0;
+    int q = __float2int_rn(fminf(fmaxf(v, -1.0f), 256.0f));
+    return (uint8_t)min(max(q, 0), 255);
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scenes, const uint32_t* __restrict__ env_scene,
+                                               const float* __restrict__ view_proj, FrameParams fp, uint32_t B,
+                                               const uint32_t* __restrict__ tri_id, uint8_t* __restrict__ out_rgb) {
+    const int HW = fp.H * fp.W;
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // HW is a multiple of 64: one env per wave
+    if (p >= (size_t)B * HW) return;
+    const uint32_t env = __builtin_amdgcn_readfirstlane((uint32_t)(p / HW));
+    const int pix = (int)(p - (size_t)env * HW);
+    const int i = pix % fp.W, j = pix / fp.W;
+    uint8_t out[3] = {0, 0, 0};
+    const uint32_t id = tri_id[p];
+    const SceneDev sc = scenes[env_scene[env]];
+    if (id != 0xFFFFFFFFu && sc.colors != nullptr && id < sc.n_tris) {
+        float M[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) M[k] = view_proj[(size_t)env * 16 + k];
+        CVert poly[2][kMaxPoly];
+        uint32_t oc_or = 0;
+        for (int k = 0; k < 3; ++k) {
+            uint32_t vi = sc.indices[3 * (size_t)id + k];
+            const float* v = sc.verts + 3 * (size_t)vi;
+            poly[0][k].c = to_clip(M, v[0], v[1], v[2]);
+            const uint8_t* col = sc.colors + 3 * (size_t)vi;
+            poly[0][k].r = (float)col[0];
+            poly[0][k].g = (float)col[1];
+            poly[0][k].b = (float)col[2];
+            oc_or |= outcode(poly[0][k].c);
+        }
+        int cnt = 3, cur = 0;
+        const int order[6] = {4, 5, 0, 1, 2, 3};
+        for (int oi = 0; oi < 6; ++oi) {
+            int k = order[oi];
+            if (!((oc_or >> k) & 1u) || cnt < 3) continue;
+            int m = 0;
+            CVert prev = poly[cur][cnt - 1];
+            float dprev = plane_dist(prev.c, k);
+            for (int q = 0; q < cnt; ++q) {
+                CVert v = poly[cur][q];
+                float dv = plane_dist(v.c, k);
+                bool cin = dv >= 0.0f, pin = dprev >= 0.0f;
+                if (cin != pin && m < kMaxPoly) {
+                    const CVert& a = cin ? v : prev;      // inside
+                    const CVert& b = cin ? prev : v;      // outside
+                    float da = cin ? dv : dprev, db = cin ? dprev : dv;
+                    float t = da / (da - db);
+                    CVert o;
+                    o.c.x = fmaf(t, b.c.x - a.c.x, a.c.x);
+                    o.c.y = fmaf(t, b.c.y - a.c.y, a.c.y);
+                    o.c.z = fmaf(t, b.c.z - a.c.z, a.c.z);
+                    o.c.w = fmaf(t, b.c.w - a.c.w, a.c.w);
+                    o.r = fmaf(t, b.r - a.r, a.r);
+                    o.g = fmaf(t, b.g - a.g, a.g);
+                    o.b = fmaf(t, b.b - a.b, a.b);
+                    poly[cur ^ 1][m++] = o;
+                }
+                if (cin && m < kMaxPoly) poly[cur ^ 1][m++] = v;
+                prev = v;
+                dprev = dv;
+            }
+            cnt = m;
+            cur ^= 1;
+        }
+        if (cnt >= 3) {
+            SVert sv[kMaxPoly];
+            bool ok = true;
+            for (int q = 0; q < cnt; ++q) {
+                ok = project(poly[cur][q].c, fp, sv[q].xy, sv[q].iw) && ok;
+                sv[q].r = poly[cur][q].r;
+                sv[q].g = poly[cur][q].g;
+                sv[q].b = poly[cur][q].b;
+            }
+            if (ok) {
+                // the fan pieces of one triangle tile it; should rounding ever make two of them
+                // cover this pixel, the nearer one is the one the z-test kept (first one on a tie)
+                float best = 0.0f;
+                bool found = false;
+                for (int q = 1; q + 1 < cnt; ++q) {
+                    float d, rgb[3];
+                    if (piece_colour(sv[0], sv[q], sv[q + 1], i, j, d, rgb) && (!found || d < best)) {
+                        found = true;
+                        best = d;
+                        out[0] = to_u8(rgb[0]);
+                        out[1] = to_u8(rgb[1]);
+                        out[2] = to_u8(rgb[2]);
+                    }
+                }
+            }
+        }
+    }
+    out_rgb[3 * p + 0] = out[0];
+    out_rgb[3 * p + 1] = out[1];
+    out_rgb[3 * p + 2] = out[2];
+}
+
+void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
+                  const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb) {
+    size_t n = (size_t)B * fp.H * fp.W;
+    hipLaunchKernelGGL(k_shade, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, scenes, env_scene, view_proj, fp, B,
+                       tri_id, out_rgb);
+}
+
+}  // namespace bps

@@ -1,0 +1,148 @@
+"""GPU edge cases and invariants of the C-ABI renderer (all inputs small and seeded)."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+NOHIT = 0xFFFFFFFF
+
+
+@pytest.fixture(scope="module")
+def room():
+    return synth.build_config(1)
+
+
+def _frames(r, ids, vp, **kw):
+    import torch
+    d, rgb, t = r.render(np.asarray(ids, np.int32), vp, want_tri_id=True, **kw)
+    torch.cuda.synchronize()
+    return d.cpu().numpy(), t.cpu().numpy().view(np.uint32)
+
+
+def test_error_paths_return_statuses(room):
+    import torch
+    import paper_2103_07013_amd as bps
+    s = room.scenes[0]
+    with bps.Renderer(max_batch=4) as r:
+        h = r.load_scene(s.vertices, s.indices)
+        out = torch.empty((8, 64, 64), dtype=torch.float32, device="cuda")
+        with pytest.raises(bps.BpsError) as e:           # B > max_batch
+            bps.bps_render(r.handle, np.zeros(8, np.int32), room.view_proj[:8], out)
+        assert e.value.status == -1
+        with pytest.raises(bps.BpsError) as e:           # unknown scene
+            bps.bps_render(r.handle, np.array([h + 5], np.int32), room.view_proj[:1], out[:1])
+        assert e.value.status == -2
+        with pytest.raises(bps.BpsError) as e:           # index out of range at load
+            r.load_scene(s.vertices[:10], s.indices)
+        assert e.value.status == -1
+        bad = s.vertices.copy()
+        bad[3, 1] = np.inf
+        with pytest.raises(bps.BpsError):                # non-finite vertex at load
+            r.load_scene(bad, s.indices)
+        r.unload_scene(h)
+        with pytest.raises(bps.BpsError) as e:           # stale handle
+            bps.bps_render(r.handle, np.array([h], np.int32), room.view_proj[:1], out[:1])
+        assert e.value.status == -2
+        with pytest.raises(bps.BpsError):
+            r.unload_scene(h)
+        # empty batch is a no-op
+        bps.bps_render(r.handle, np.zeros(0, np.int32), room.view_proj[:0], out[:0])
+        h2 = r.load_scene(s.vertices, s.indices)         # slot is reused
+        assert h2 == h
+    with bps.Renderer(max_batch=2, mode=bps.MODE_RGBD) as r:
+        h = r.load_scene(s.vertices, s.indices)          # no colours
+        rgb = torch.empty((1, 64, 64, 3), dtype=torch.uint8, device="cuda")
+        with pytest.raises(bps.BpsError) as e:
+            bps.bps_render(r.handle, np.array([h], np.int32), room.view_proj[:1], out[:1], out_rgb=rgb)
+        assert e.value.status == -1
+
+
+def test_batch_independence_two_handles_and_determinism(room):
+    import paper_2103_07013_amd as bps
+    s = room.scenes[0]
+    with bps.Renderer(max_batch=16) as r:
+        h1 = r.load_scene(s.vertices, s.indices)
+        h2 = r.load_scene(s.vertices, s.indices)
+        d_all, t_all = _frames(r, [h1] * 16, room.view_proj)
+        for b in (0, 7, 15):                             # an environment alone == its slot in the batch
+            d1, t1 = _frames(r, [h1], room.view_proj[b:b + 1])
+            assert np.array_equal(d1[0], d_all[b]) and np.array_equal(t1[0], t_all[b])
+        d2, t2 = _frames(r, [h2] * 16, room.view_proj)   # same mesh under another handle
+        assert np.array_equal(d2, d_all) and np.array_equal(t2, t_all)
+        dm, tm = _frames(r, [h1, h2] * 8, room.view_proj)
+        assert np.array_equal(dm, d_all) and np.array_equal(tm, t_all)
+        for _ in range(5):                               # run-to-run determinism
+            d3, t3 = _frames(r, [h1] * 16, room.view_proj)
+            assert np.array_equal(d3, d_all) and np.array_equal(t3, t_all)
+
+
+def test_split_and_unsplit_frames_agree_and_buffer_is_left_clean(room):
+    import paper_2103_07013_amd as bps
+    s = room.scenes[0]
+    with bps.Renderer(max_batch=16, splits=1) as r1, bps.Renderer(max_batch=16, splits=4) as r4:
+        a = r1.load_scene(s.vertices, s.indices)
+        b = r4.load_scene(s.vertices, s.indices)
+        d1, t1 = _frames(r1, [a] * 16, room.view_proj)
+        for rep in range(3):                             # the merge buffer must come back empty every time
+            d4, t4 = _frames(r4, [b] * 16, room.view_proj)
+            assert np.array_equal(d1, d4) and np.array_equal(t1, t4), rep
+        # a smaller, different request after a larger one
+        d4, t4 = _frames(r4, [b] * 3, room.view_proj[5:8])
+        assert np.array_equal(d1[5:8], d4) and np.array_equal(t1[5:8], t4)
+
+
+def test_non_finite_and_degenerate_matrices_give_background(room):
+    import paper_2103_07013_amd as bps
+    s = room.scenes[0]
+    vp = room.view_proj[:4].copy()
+    vp[0, 1, 2] = np.nan
+    vp[1] = 0.0
+    vp[2, 3, :] = np.inf
+    with bps.Renderer(max_batch=4, background_depth=-1.0) as r:
+        h = r.load_scene(s.vertices, s.indices)
+        d, t = _frames(r, [h] * 4, vp)
+    for b in (0, 1, 2):
+        assert np.all(t[b] == NOHIT) and np.all(d[b] == -1.0)
+    assert (t[3] != NOHIT).all()
+
+
+def test_tiny_meshes_and_hand_enumerated_fill_rule():
+    """One triangle, fewer triangles than lanes, and the 8x8 hand-enumerated fixtures through the GPU."""
+    import os
+    import paper_2103_07013_amd as bps
+    here = os.path.dirname(os.path.abspath(__file__))
+    M = np.array([[0.25, 0, 0, -1], [0, 0.25, 0, -1], [0, 0, 0, 0.5], [0, 0, 0, 1]], np.float32)  # pixel k at x in [k, k+1)
+    for name in ("fill_rule_upper_left.txt", "fill_rule_lower_right.txt", "fill_rule_centre_corners.txt"):
+        tris, rows = [], []
+        for line in open(os.path.join(here, "golden", name)):
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line.startswith("tri"):
+                tris.append([int(x) for x in line.split()[1:]])
+            else:
+                rows.append([int(ch) for ch in line])
+        xy = np.array(tris, np.float64).reshape(-1, 3, 2) / 256.0
+        v = np.concatenate([xy, np.zeros((xy.shape[0], 3, 1))], 2).reshape(-1, 3).astype(np.float32)
+        idx = np.arange(v.shape[0], dtype=np.uint32).reshape(-1, 3)
+        with bps.Renderer(max_batch=1, height=8, width=8) as r:
+            h = r.load_scene(v, idx)
+            d, t = _frames(r, [h], M[None])
+        assert np.array_equal((t[0] != NOHIT).astype(np.uint32), np.array(rows, np.uint32)), name
+        assert np.all(d[0][t[0] != NOHIT] == 1.0)
+
+
+def test_device_and_host_matrices_and_explicit_stream(room):
+    import torch
+    import paper_2103_07013_amd as bps
+    s = room.scenes[0]
+    with bps.Renderer(max_batch=16) as r:
+        h = r.load_scene(s.vertices, s.indices)
+        d0, t0 = _frames(r, [h] * 16, room.view_proj)
+        side = torch.cuda.Stream()
+        vp = torch.from_numpy(room.view_proj).cuda()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            d1, t1 = _frames(r, [h] * 16, vp, stream=side)
+        assert np.array_equal(d0, d1) and np.array_equal(t0, t1)

@@ -1,0 +1,65 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the whole
+batch is rendered on the GPU, a strided sample of environments is checked against the oracle
+pixel by pixel, and properties that hold at any size are checked on every frame."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+NOHIT = 0xFFFFFFFF
+
+
+def _run(w, sample, rgbd=False):
+    import torch
+    import oracle
+    import paper_2103_07013_amd as bps
+    mode = bps.MODE_RGBD if rgbd else bps.MODE_DEPTH
+    with bps.Renderer(max_batch=w.B, height=w.H, width=w.W, mode=mode) as r:
+        handles = [r.load_scene(s.vertices, s.indices, s.colors if rgbd else None) for s in w.scenes]
+        ids = np.array([handles[k] for k in w.scene_ids], np.int32)
+        vp = torch.from_numpy(w.view_proj).cuda()
+        depth, rgb, tid = r.render(ids, vp, want_tri_id=True)
+        torch.cuda.synchronize()
+        gd, gi = depth.cpu().numpy(), tid.cpu().numpy().view(np.uint32)
+        grgb = rgb.cpu().numpy() if rgbd else None
+    sel = np.asarray(sample)
+    ref = oracle.render_batch(w.scenes, w.scene_ids[sel], w.view_proj[sel], w.H, w.W, rgbd=rgbd)
+    assert np.array_equal(gi[sel], ref["tri_id"]), "coverage / ids differ"
+    assert np.all(np.abs(gd[sel] - ref["depth"]) <= 1e-5 * np.abs(ref["depth"]))
+    if rgbd:
+        diff = np.abs(grgb[sel].astype(int) - ref["rgb"].astype(int))
+        assert diff.max() <= 1, f"colour off by {diff.max()}"
+        assert (diff > 0).mean() < 1e-3
+        assert np.all(grgb[gi == NOHIT] == 0)
+    # properties of every frame
+    hit = gi != NOHIT
+    T = np.array([w.scenes[k].T for k in w.scene_ids], np.uint32)
+    assert np.all(gi[hit] < np.broadcast_to(T[:, None, None], gi.shape)[hit])
+    assert np.all(gd[~hit] == 0.0)
+    assert gd[hit].min() >= 0.01 and gd[hit].max() <= 20.0 * (1 + 1e-6)
+    assert hit.mean() > 0.9
+    return gd, gi
+
+
+def test_config3_headline_full_batch():
+    w = synth.build_config(3)
+    assert w.B == 1024 and len(w.scenes) == 4
+    _run(w, sample=np.arange(0, 1024, 85)[:12] + np.arange(12) % 4)
+
+
+def test_config2_full_batch():
+    w = synth.build_config(2)
+    _run(w, sample=np.arange(0, 256, 16))
+
+
+def test_config4_rgbd_full_batch():
+    w = synth.build_config(4)
+    assert w.rgbd and w.B == 1024 and len(w.scenes) == 8
+    _run(w, sample=np.arange(0, 1024, 128) + np.arange(8), rgbd=True)
+
+
+def test_config5_128x128_large_batch():
+    w = synth.build_config(5)
+    assert w.B == 4096 and w.H == 128 and len(w.scenes) == 16
+    _run(w, sample=np.arange(0, 4096, 512) + np.arange(8) * 3)
