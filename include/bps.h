@@ -43,6 +43,10 @@ enum {
 
 enum { BPS_MODE_DEPTH = 0, BPS_MODE_RGBD = 1 };
 
+/* bps_config.flags.  Cluster culling is the paper's frustum culling of geometry chunks
+ * (Sec. 3.2 "Pipelined geometry culling"); it never changes a frame, only the work done. */
+enum { BPS_FLAG_NO_CLUSTER_CULL = 1 };
+
 typedef struct {
     int32_t device;          /* HIP device ordinal */
     int32_t max_batch;       /* largest B accepted by bps_render (>= 1) */
@@ -51,6 +55,7 @@ typedef struct {
     float background_depth;  /* written where no triangle covers the pixel centre */
     int32_t splits;          /* work-groups per environment; 0 = choose from B and the device */
     int32_t threads;         /* work-group size: 0 = default, else 256, 512 or 1024 */
+    uint32_t flags;          /* BPS_FLAG_* bits, 0 = defaults */
 } bps_config;
 
 /* Create a renderer on cfg->device.  *out receives the handle.  Allocates the device scene
@@ -106,6 +111,16 @@ bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *
 bps_status bps_set_profiling(bps_renderer *r, int32_t enable);
 bps_status bps_last_kernel_ms(bps_renderer *r, float *ms);
 bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total_ms);
+
+/* Diagnostics: when enabled, the raster kernel tallies its work into a device block that
+ * bps_read_diagnostics copies out after waiting for the device:
+ *   out[0] clusters whose bounds were tested       out[1] clusters that passed the bounds test
+ *   out[2] clusters that reached the triangle phase out[3] triangles sent to the clipper
+ *   out[4] sum and out[5] maximum over wavefronts of their run time in 100 MHz ticks
+ *   out[8 + g] run time of work-group g's first wavefront.
+ * `capacity` is the room in `out` (in words), *written the number of words copied. */
+bps_status bps_set_diagnostics(bps_renderer *r, int32_t enable);
+bps_status bps_read_diagnostics(bps_renderer *r, uint64_t *out, uint32_t capacity, uint32_t *written);
 
 /* Facts about a loaded scene and the launch plan, for benchmarks and tests.
  * what: 0 = clusters in the scene, 1 = triangles, 2 = vertices, 3 = device bytes held,

@@ -9,8 +9,9 @@ import numpy as np
 from . import build as _build
 
 MODE_DEPTH, MODE_RGBD = 0, 1
+FLAG_NO_CLUSTER_CULL = 1
 EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
-           "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_query", "bps_last_error"]
+           "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 
 
 class BpsError(RuntimeError):
@@ -22,7 +23,7 @@ class BpsError(RuntimeError):
 class bps_config(ctypes.Structure):
     _fields_ = [("device", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("height", ctypes.c_int32),
                 ("width", ctypes.c_int32), ("mode", ctypes.c_int32), ("background_depth", ctypes.c_float),
-                ("splits", ctypes.c_int32), ("threads", ctypes.c_int32)]
+                ("splits", ctypes.c_int32), ("threads", ctypes.c_int32), ("flags", ctypes.c_uint32)]
 
 
 _lib = None
@@ -55,6 +56,10 @@ def load_library():
     lib.bps_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.bps_kernel_ms_total.restype = ctypes.c_int32
     lib.bps_kernel_ms_total.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_float)]
+    lib.bps_set_diagnostics.restype = ctypes.c_int32
+    lib.bps_set_diagnostics.argtypes = [vp, ctypes.c_int32]
+    lib.bps_read_diagnostics.restype = ctypes.c_int32
+    lib.bps_read_diagnostics.argtypes = [vp, vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32)]
     lib.bps_query.restype = ctypes.c_int32
     lib.bps_query.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_uint64)]
     lib.bps_last_error.restype = ctypes.c_char_p
@@ -73,9 +78,9 @@ def _check(status, handle):
 
 
 def bps_create(device=0, max_batch=1024, height=64, width=64, mode=MODE_DEPTH, background_depth=0.0, splits=0,
-               threads=0):
+               threads=0, flags=0):
     lib = load_library()
-    cfg = bps_config(device, max_batch, height, width, mode, background_depth, splits, threads)
+    cfg = bps_config(device, max_batch, height, width, mode, background_depth, splits, threads, flags)
     h = ctypes.c_void_p()
     _check(lib.bps_create(ctypes.byref(cfg), ctypes.byref(h)), None)
     return h
@@ -177,6 +182,18 @@ def bps_kernel_ms_total(handle):
     return int(n.value), float(ms.value)
 
 
+def bps_set_diagnostics(handle, enable=True):
+    _check(load_library().bps_set_diagnostics(handle, 1 if enable else 0), handle)
+
+
+def bps_read_diagnostics(handle, capacity=1 << 16):
+    """uint64 array: 8 counters then one duration per work-group (see include/bps.h)."""
+    out = np.zeros(capacity, np.uint64)
+    n = ctypes.c_uint32(0)
+    _check(load_library().bps_read_diagnostics(handle, out.ctypes.data, capacity, ctypes.byref(n)), handle)
+    return out[:int(n.value)]
+
+
 def bps_query(handle, scene, what):
     v = ctypes.c_uint64(0)
     _check(load_library().bps_query(handle, int(scene), int(what), ctypes.byref(v)), handle)
@@ -187,9 +204,9 @@ class Renderer:
     """Convenience owner of one bps_renderer handle (same calls, object style)."""
 
     def __init__(self, max_batch, height=64, width=64, mode=MODE_DEPTH, device=0, background_depth=0.0, splits=0,
-                 threads=0):
+                 threads=0, flags=0):
         self.H, self.W, self.mode, self.device = height, width, mode, device
-        self.handle = bps_create(device, max_batch, height, width, mode, background_depth, splits, threads)
+        self.handle = bps_create(device, max_batch, height, width, mode, background_depth, splits, threads, flags)
 
     def load_scene(self, vertices, indices, colors=None):
         return bps_load_scene(self.handle, vertices, indices, colors)

@@ -27,7 +27,7 @@ thread_local std::string g_create_error = "";
 struct HostScene {
     bool live = false;
     bps::SceneDev dev{};
-    void* allocs[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    void* allocs[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     uint64_t bytes = 0;
     bool has_colors = false;
 };
@@ -47,6 +47,7 @@ struct bps_renderer {
     int device = 0;
     int num_cu = 0;
     int threads = 512;
+    int round_blocks = 32;
     size_t lds = 0;
     size_t max_lds = 0;
     std::string error = "";
@@ -56,6 +57,9 @@ struct bps_renderer {
     int ring_next = 0;
     unsigned long long* gvis = nullptr;   // [max_batch][H][W], only for split frames
     uint32_t* ids = nullptr;              // [max_batch][H][W], RGB-D requests without a caller id buffer
+    unsigned long long* d_stats = nullptr;   // diagnostics block: 8 counters + one duration per work-group
+    size_t stats_cap = 0;
+    bool want_stats = false;
     std::vector<hipEvent_t> ev;           // profiling: pairs (start, stop), one pair per request
     size_t ev_used = 0;
     bool profiling = false;
@@ -102,7 +106,7 @@ int plan_splits(const bps_renderer* r, uint32_t B, uint32_t min_clusters) {
     int want_groups = 4 * r->num_cu;
     int s = 1;
     if ((int)B < 2 * r->num_cu) s = (want_groups + (int)B - 1) / (int)B;
-    int max_s = std::max(1, (int)(min_clusters / (uint32_t)(4 * waves)));   // >= 4 clusters per wave
+    int max_s = std::max(1, (int)(min_clusters / (uint32_t)(8 * waves)));   // >= 8 clusters per wave
     return std::max(1, std::min(s, max_s));
 }
 
@@ -123,6 +127,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
     if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 512 && cfg->threads != 1024)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 512 or 1024");
     if (cfg->splits < 0) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be >= 0");
+    if (cfg->flags & ~(uint32_t)BPS_FLAG_NO_CLUSTER_CULL) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
         return fail(nullptr, BPS_ERR_HIP, "bps_create: no HIP device available (this library has no CPU path)");
@@ -148,20 +153,24 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         if (hipDeviceGetAttribute(&lds_optin, hipDeviceAttributeSharedMemPerBlockOptin, r->device) != hipSuccess) lds_optin = 0;
         (void)hipGetLastError();
         r->max_lds = std::max<size_t>(prop.sharedMemPerBlock, (size_t)std::max(lds_optin, 0));
-        // largest work-group whose LDS footprint fits
+        // preferred work-group size whose LDS footprint fits, with the longest survivor list that fits
         const int order[3] = {512, 256, 1024};
+        const int rounds[3] = {32, 16, 8};
         r->threads = 0;
-        if (cfg->threads) {
-            if (bps::lds_bytes(cfg->height, cfg->width, cfg->threads) <= r->max_lds) r->threads = cfg->threads;
-        } else {
-            for (int t : order)
-                if (bps::lds_bytes(cfg->height, cfg->width, t) <= r->max_lds) { r->threads = t; break; }
+        for (int rb : rounds) {
+            if (cfg->threads) {
+                if (bps::lds_bytes(cfg->height, cfg->width, cfg->threads, rb) <= r->max_lds) r->threads = cfg->threads;
+            } else {
+                for (int t : order)
+                    if (bps::lds_bytes(cfg->height, cfg->width, t, rb) <= r->max_lds) { r->threads = t; break; }
+            }
+            if (r->threads) { r->round_blocks = rb; break; }
         }
         if (!r->threads)
             return fail(r, BPS_ERR_UNSUPPORTED, "bps_create: a %dx%d frame needs %zu bytes of LDS, device offers %zu",
-                        cfg->height, cfg->width, bps::lds_bytes(cfg->height, cfg->width, cfg->threads ? cfg->threads : 256),
+                        cfg->height, cfg->width, bps::lds_bytes(cfg->height, cfg->width, cfg->threads ? cfg->threads : 256, 8),
                         r->max_lds);
-        r->lds = bps::lds_bytes(cfg->height, cfg->width, r->threads);
+        r->lds = bps::lds_bytes(cfg->height, cfg->width, r->threads, r->round_blocks);
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
         BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
@@ -186,6 +195,7 @@ void bps_destroy(bps_renderer* r) {
     }
     if (r->gvis) (void)hipFree(r->gvis);
     if (r->ids) (void)hipFree(r->ids);
+    if (r->d_stats) (void)hipFree(r->d_stats);
     if (r->d_scenes) (void)hipFree(r->d_scenes);
     for (hipEvent_t e : r->ev) (void)hipEventDestroy(e);
     delete r;
@@ -244,10 +254,18 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
         hs.dev.colors = (const uint8_t*)p;
         hs.has_colors = true;
     }
+    {   // bounds as six planes of c_stride floats so that 64 lanes read 64 consecutive clusters
+        const uint32_t stride = (cs.count + 63u) & ~63u;
+        std::vector<float> planes((size_t)6 * stride, 0.0f);
+        for (uint32_t c = 0; c < cs.count; ++c)
+            for (int a = 0; a < 6; ++a) planes[(size_t)a * stride + c] = cs.bounds[(size_t)c * 6 + a];
+        if ((st = upload(6, planes.data(), planes.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
+        hs.dev.cbounds = (const float*)p;
+        hs.dev.c_stride = stride;
+    }
     hs.dev.n_clusters = cs.count;
     hs.dev.n_tris = T;
     hs.dev.n_verts = V;
-    hs.dev.live = 1;
     hs.live = true;
     hipError_t e = hipMemcpy(r->d_scenes + slot, &hs.dev, sizeof(bps::SceneDev), hipMemcpyHostToDevice);
     if (e != hipSuccess) { free_scene(hs); return fail(r, BPS_ERR_HIP, "bps_load_scene: scene table update: %s", hipGetErrorString(e)); }
@@ -327,12 +345,13 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         for (uint32_t k = 0; k < B; ++k) {
             uint32_t b = order[k];
             uint32_t C = r->scenes[scene_ids[b]].dev.n_clusters;
+            (void)C;
             for (int s = 0; s < S; ++s) {
                 bps::WorkItem it;
                 it.env = b;
                 it.scene = (uint32_t)scene_ids[b];
-                it.c_begin = (uint32_t)((uint64_t)C * s / S);
-                it.c_end = (uint32_t)((uint64_t)C * (s + 1) / S);
+                it.split = (uint32_t)s;
+                it.n_splits = (uint32_t)S;
                 sorted.push_back(it);
             }
         }
@@ -410,7 +429,22 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     fp.ymax = 2.0f * fp.sy + 64.0f;
     fp.background = r->cfg.background_depth;
     fp.merge = S > 1 ? 1 : 0;
+    fp.cull = (r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL) ? 0 : 1;
+    fp.round_blocks = r->round_blocks;
 
+    unsigned long long* d_stats = nullptr;
+    if (r->want_stats) {
+        if (r->stats_cap < 8 + n_items) {
+            if (r->d_stats) (void)hipFree(r->d_stats);
+            r->d_stats = nullptr;
+            r->stats_cap = 0;
+            BPS_HIP(r, hipMalloc((void**)&r->d_stats, (8 + n_items) * sizeof(unsigned long long)));
+            r->stats_cap = 8 + n_items;
+        }
+        hipLaunchKernelGGL(bps::k_zero_words, dim3((unsigned)((8 + n_items + 255) / 256)), dim3(256), 0, stream, r->d_stats,
+                           8 + n_items);
+        d_stats = r->d_stats;
+    }
     hipEvent_t ev_stop = nullptr;
     if (r->profiling && r->ev_used + 2 <= 2 * kMaxProfiled) {
         while (r->ev.size() < r->ev_used + 2) {
@@ -423,7 +457,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         r->ev_used += 2;
     }
     bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, d_items, d_vp, fp, r->gvis, out_depth,
-                       out_tri_id);
+                       out_tri_id, d_stats);
     BPS_HIP(r, hipGetLastError());
     if (S > 1) {
         size_t n = (size_t)B * HW;
@@ -470,6 +504,23 @@ bps_status bps_kernel_ms_total(bps_renderer* r, uint32_t* launches, float* total
     *launches = (uint32_t)(r->ev_used / 2);
     *total_ms = sum;
     r->ev_used = 0;
+    return BPS_OK;
+}
+
+bps_status bps_set_diagnostics(bps_renderer* r, int32_t enable) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    r->want_stats = enable != 0;
+    return BPS_OK;
+}
+
+bps_status bps_read_diagnostics(bps_renderer* r, uint64_t* out, uint32_t capacity, uint32_t* written) {
+    if (!r || !out || !written) return BPS_ERR_INVALID_ARG;
+    if (!r->d_stats) return fail(r, BPS_ERR_INVALID_ARG, "bps_read_diagnostics: no request ran with diagnostics enabled");
+    BPS_HIP(r, hipSetDevice(r->device));
+    BPS_HIP(r, hipDeviceSynchronize());
+    size_t n = std::min<size_t>(capacity, 8 + (size_t)r->last_groups);
+    BPS_HIP(r, hipMemcpy(out, r->d_stats, n * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    *written = (uint32_t)n;
     return BPS_OK;
 }
 

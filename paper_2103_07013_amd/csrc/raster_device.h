@@ -12,6 +12,13 @@ namespace dev {
 
 typedef unsigned long long u64;
 
+// Loads through pointers that arrive inside structs would otherwise be generic ("flat") accesses.
+#define BPS_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ const BPS_GLOBAL T* gptr(const T* p) {
+    return (const BPS_GLOBAL T*)p;
+}
+
 __device__ __forceinline__ u64 ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
 __device__ __forceinline__ uint32_t rank_below(u64 mask) {
@@ -30,10 +37,19 @@ __device__ __forceinline__ float bcast_f(float v, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
+// Snapped screen coordinates travel as two signed 16-bit halves, x low and y high, relative to
+// kOrigin = 64 pixels, so that the whole range [-64, 256*128 + 64] of a 128-pixel axis fits and
+// bounding boxes can be computed with packed 16-bit instructions.
+__device__ __forceinline__ uint32_t pack_xy(int X, int Y) {
+    return ((uint32_t)(X - kOrigin) & 0xFFFFu) | ((uint32_t)(Y - kOrigin) << 16);
+}
+__device__ __forceinline__ int unpack_x(uint32_t xy) { return (int)(short)(xy & 0xFFFFu); }
+__device__ __forceinline__ int unpack_y(uint32_t xy) { return (int)xy >> 16; }
+
 // ---------------------------------------------------------------------------------------------
 // Triangle in snapped screen space, oriented so that A2 > 0, with its edge set-up.
 struct Setup {
-    int X0, Y0, X1, Y1, X2, Y2;   // biased 1/256-px coordinates
+    int X0, Y0, X1, Y1, X2, Y2;   // 1/256-px coordinates relative to kOrigin
     float iw0, iw1, iw2;
     int A2;
     int dx0, dy0, dx1, dy1, dx2, dy2;   // edge k is opposite vertex k
@@ -45,9 +61,9 @@ __device__ __forceinline__ int tl_bias(int dx, int dy) { return (dy < 0 || (dy =
 
 __device__ __forceinline__ Setup make_setup(uint32_t xy0, uint32_t xy1, uint32_t xy2, float iw0, float iw1, float iw2) {
     Setup s;
-    s.X0 = (int)(xy0 & 0xFFFFu); s.Y0 = (int)(xy0 >> 16);
-    s.X1 = (int)(xy1 & 0xFFFFu); s.Y1 = (int)(xy1 >> 16);
-    s.X2 = (int)(xy2 & 0xFFFFu); s.Y2 = (int)(xy2 >> 16);
+    s.X0 = unpack_x(xy0); s.Y0 = unpack_y(xy0);
+    s.X1 = unpack_x(xy1); s.Y1 = unpack_y(xy1);
+    s.X2 = unpack_x(xy2); s.Y2 = unpack_y(xy2);
     s.iw0 = iw0; s.iw1 = iw1; s.iw2 = iw2;
     int a2 = __mul24(s.X1 - s.X0, s.Y2 - s.Y0) - __mul24(s.X2 - s.X0, s.Y1 - s.Y0);
     s.swapped = a2 < 0;
@@ -70,11 +86,11 @@ __device__ __forceinline__ Setup make_setup(uint32_t xy0, uint32_t xy1, uint32_t
 
 // Coverage test and z-test of pixel (i, j) against one set-up triangle.
 __device__ __forceinline__ void shade_pixel(const Setup& s, int i, int j, bool active, uint32_t id, u64* vis, int W) {
-    int px = (i << 8) + 128 + kBias, py = (j << 8) + 128 + kBias;
+    int px = (i << 8) + 128 - kOrigin, py = (j << 8) + 128 - kOrigin;
     int E0 = __mul24(s.dx0, py - s.Y1) - __mul24(s.dy0, px - s.X1);
     int E1 = __mul24(s.dx1, py - s.Y2) - __mul24(s.dy1, px - s.X2);
     int E2 = __mul24(s.dx2, py - s.Y0) - __mul24(s.dy2, px - s.X0);
-    bool in = active && (((E0 + s.b0) | (E1 + s.b1) | (E2 + s.b2)) >= 0);
+    bool in = active && s.A2 != 0 && (((E0 + s.b0) | (E1 + s.b1) | (E2 + s.b2)) >= 0);
     if (in) {
         float e0 = (float)E0, e1 = (float)E1, e2 = (float)E2;
         float num = fmaf(e2, s.iw2, fmaf(e1, s.iw1, e0 * s.iw0));
@@ -108,6 +124,12 @@ __device__ __forceinline__ float plane_dist(const Clip4& v, int k) {
     }
 }
 
+// x*0 is 0 for every finite x and NaN otherwise, so one fma chain tests all four coordinates.
+__device__ __forceinline__ bool all_finite(const Clip4& c) {
+    float t = fmaf(c.x, 0.0f, fmaf(c.y, 0.0f, fmaf(c.z, 0.0f, c.w * 0.0f)));
+    return t == t;
+}
+
 __device__ __forceinline__ uint32_t outcode(const Clip4& c) {
     uint32_t oc = 0;
     oc |= !(c.w + c.x >= 0.0f) ? 1u : 0u;
@@ -116,8 +138,7 @@ __device__ __forceinline__ uint32_t outcode(const Clip4& c) {
     oc |= !(c.w - c.y >= 0.0f) ? 8u : 0u;
     oc |= !(c.z >= 0.0f) ? 16u : 0u;
     oc |= !(c.w - c.z >= 0.0f) ? 32u : 0u;
-    bool fin = __builtin_isfinite(c.x) && __builtin_isfinite(c.y) && __builtin_isfinite(c.z) && __builtin_isfinite(c.w);
-    if (!fin) oc |= kInvalid;
+    if (!all_finite(c)) oc |= kInvalid;
     return oc;
 }
 
@@ -127,8 +148,7 @@ __device__ __forceinline__ bool project(const Clip4& c, const FrameParams& fp, u
     float xn = c.x * iw, yn = c.y * iw;
     float fx = fmaf(xn, fp.sx, fp.sx), fy = fmaf(yn, fp.sy, fp.sy);
     bool ok = (c.w > 0.0f) && fx >= -64.0f && fx <= fp.xmax && fy >= -64.0f && fy <= fp.ymax;
-    int X = __float2int_rn(fx) + kBias, Y = __float2int_rn(fy) + kBias;
-    xy = ((uint32_t)X & 0xFFFFu) | ((uint32_t)Y << 16);
+    xy = pack_xy(__float2int_rn(fx), __float2int_rn(fy));
     return ok;
 }
 

@@ -26,14 +26,17 @@ struct SceneDev {
     const float* cverts;       // [C][3][64] cluster vertex positions, x then y then z
     const uint32_t* ctris;     // [C][128]   packed local indices, count in bits 24..31 of word 0
     const uint32_t* ctri_id;   // [C][128]   original triangle row
+    const float* cbounds;      // [6][c_stride] cluster bounds: min x, y, z then max x, y, z
     const float* verts;        // [V][3]     original arrays, used when shading
     const uint32_t* indices;   // [T][3]
     const uint8_t* colors;     // [V][3] or null
-    uint32_t n_clusters, n_tris, n_verts, live;
+    uint32_t n_clusters, n_tris, n_verts, c_stride;
 };
 
+// One work-group's share: environment `env`, and of its scene the 64-cluster blocks
+// split, split + n_splits, split + 2 n_splits, ...
 struct WorkItem {
-    uint32_t env, scene, c_begin, c_end;
+    uint32_t env, scene, split, n_splits;
 };
 
 struct FrameParams {
@@ -42,33 +45,39 @@ struct FrameParams {
     float xmax, ymax;      // 2*sx + 64, 2*sy + 64
     float background;
     int32_t merge;         // 0: resolve straight to the output; 1: atomic-min into the global buffer
+    int32_t cull;          // 1: skip clusters whose bounds lie outside one frustum plane
+    int32_t round_blocks;  // 64-cluster blocks tested per round (capacity of the survivor list / 64)
 };
 
 constexpr unsigned long long kEmptyKey = ~0ull;
-constexpr int kBias = 64;              // packed screen coordinates are stored + 64
+constexpr int kOrigin = 16384;         // packed screen coordinates are stored relative to pixel 64
 constexpr int kSmallMax = 4;           // pixel centres a "small" triangle may touch
 constexpr uint32_t kInvalid = 0x40u;   // outcode bit: vertex unusable, drop its triangles
 
-// per-wave LDS block: 64 staged vertices (16 B each), small queue 8 x 64 words, clip queue 192 words
-constexpr uint32_t kWaveLdsBytes = 64 * 16 + 8 * 64 * 4 + 192 * 4;
+// per-wave LDS block: 64 staged vertices (8 B + 4 B outcode each), small queue 8 x 64 words,
+// clip queue 192 words
+constexpr uint32_t kWaveLdsBytes = 64 * 12 + 8 * 64 * 4 + 192 * 4;
 
-__host__ __device__ inline size_t lds_bytes(int H, int W, int threads) {
-    return (size_t)H * W * 8 + (size_t)(threads / 64) * kWaveLdsBytes;
+// visibility buffer, per-wave blocks, survivor list (2 B per cluster of a round), two counters
+__host__ __device__ inline size_t lds_bytes(int H, int W, int threads, int round_blocks) {
+    return (size_t)H * W * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)round_blocks * 128 + 16;
 }
 
 template <int NT>
 __global__ void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                          const float* __restrict__ view_proj, FrameParams fp, unsigned long long* __restrict__ gvis,
-                         float* __restrict__ out_depth, uint32_t* __restrict__ out_id);
+                         float* __restrict__ out_depth, uint32_t* __restrict__ out_id,
+                         unsigned long long* __restrict__ stats);
 
 __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float background,
                           float* __restrict__ out_depth, uint32_t* __restrict__ out_id);
 
 __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n);
+__global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n);
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
-                   uint32_t* out_id);
+                   uint32_t* out_id, unsigned long long* stats);
 hipError_t prepare_raster(int threads, size_t lds);
 void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
                   const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb);

@@ -16,7 +16,8 @@ using namespace dev;
 // ---------------------------------------------------------------------------------------------
 // Per-wave state kept in LDS.
 struct WaveLds {
-    float4* stage;      // [64] staged vertices of the current cluster: (xy bits, 1/w, outcode bits, -)
+    float2* stage;      // [64] staged vertices of the current cluster: (packed xy bits, 1/w)
+    uint32_t* stage_oc; // [64] their outcodes
     uint32_t* smallq;   // [8][64] struct-of-arrays: xy0 xy1 xy2 iw0 iw1 iw2 id box
     uint32_t* clipq;    // [192] cluster << 7 | slot
 };
@@ -94,25 +95,34 @@ __device__ __forceinline__ void raster_large(uint32_t xy0, uint32_t xy1, uint32_
     }
 }
 
+typedef short short2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ short2v as_s2(uint32_t v) { return __builtin_bit_cast(short2v, v); }
+__device__ __forceinline__ uint32_t as_u32(short2v v) { return __builtin_bit_cast(uint32_t, v); }
+
 // Bounding-box cull, classification and hand-off of one candidate triangle per lane.
+// Works on both axes at once with packed 16-bit arithmetic.  Pixel i has its centre at
+// 256 (i - 64) + 128 in packed coordinates, so the first centre at or right of x is
+// (x + 127) >> 8 and the last centre at or left of x is (x - 128) >> 8 (both minus 64).
 // id_ptr is only dereferenced by lanes whose triangle can touch a pixel centre.
 __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool valid, uint32_t xy0, uint32_t xy1,
-                                     uint32_t xy2, float iw0, float iw1, float iw2, const uint32_t* id_ptr, int lane,
-                                     u64* vis, int H, int W) {
-    int X0 = (int)(xy0 & 0xFFFFu), Y0 = (int)(xy0 >> 16);
-    int X1 = (int)(xy1 & 0xFFFFu), Y1 = (int)(xy1 >> 16);
-    int X2 = (int)(xy2 & 0xFFFFu), Y2 = (int)(xy2 >> 16);
-    int minX = min(X0, min(X1, X2)), maxX = max(X0, max(X1, X2));
-    int minY = min(Y0, min(Y1, Y2)), maxY = max(Y0, max(Y1, Y2));
-    // pixel centres 256 i + 128 (+ bias) inside the closed box
-    int i_lo = max((minX - kBias + 127) >> 8, 0), i_hi = min((maxX - kBias - 128) >> 8, W - 1);
-    int j_lo = max((minY - kBias + 127) >> 8, 0), j_hi = min((maxY - kBias - 128) >> 8, H - 1);
-    int a2 = __mul24(X1 - X0, Y2 - Y0) - __mul24(X2 - X0, Y1 - Y0);
-    valid = valid && i_lo <= i_hi && j_lo <= j_hi && a2 != 0;
+                                     uint32_t xy2, float iw0, float iw1, float iw2, const BPS_GLOBAL uint32_t* id_ptr,
+                                     int lane, u64* vis, int H, int W) {
+    short2v a = as_s2(xy0), b = as_s2(xy1), c = as_s2(xy2);
+    short2v mn = __builtin_elementwise_min(a, __builtin_elementwise_min(b, c));
+    short2v mx = __builtin_elementwise_max(a, __builtin_elementwise_max(b, c));
+    short2v lo = (mn + (short)127) >> (short)8;
+    short2v hi = (mx - (short)128) >> (short)8;
+    short2v lo_clamp = {(short)-64, (short)-64};
+    short2v hi_clamp = {(short)(W - 65), (short)(H - 65)};
+    lo = __builtin_elementwise_max(lo, lo_clamp);
+    hi = __builtin_elementwise_min(hi, hi_clamp);
+    short2v ext = hi - lo;                              // both halves >= 0: some pixel centre is inside
+    valid = valid && (as_u32(ext) & 0x80008000u) == 0;
     u64 vmask = ballot64(valid);
     if (vmask == 0) return;
     uint32_t id = valid ? *id_ptr : 0u;
-    int nx = i_hi - i_lo + 1, ny = j_hi - j_lo + 1;
+    int nx = (int)ext.x + 1, ny = (int)ext.y + 1;
+    int i_lo = (int)lo.x + 64, j_lo = (int)lo.y + 64;
     bool small = valid && nx * ny <= kSmallMax;
     uint32_t box = (uint32_t)i_lo | ((uint32_t)j_lo << 8) | ((uint32_t)nx << 16) | ((uint32_t)ny << 24);
     push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, id, box, lane, vis, W);
@@ -120,12 +130,43 @@ __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool va
     while (big) {
         int src = __builtin_ctzll(big);
         big &= big - 1;
+        int bi = bcast_i(i_lo, src), bj = bcast_i(j_lo, src);
         raster_large((uint32_t)bcast_i((int)xy0, src), (uint32_t)bcast_i((int)xy1, src), (uint32_t)bcast_i((int)xy2, src),
-                     bcast_f(iw0, src), bcast_f(iw1, src), bcast_f(iw2, src), (uint32_t)bcast_i((int)id, src),
-                     bcast_i(i_lo, src), bcast_i(i_hi, src), bcast_i(j_lo, src), bcast_i(j_hi, src), lane, vis, W);
+                     bcast_f(iw0, src), bcast_f(iw1, src), bcast_f(iw2, src), (uint32_t)bcast_i((int)id, src), bi,
+                     bi + bcast_i(nx, src) - 1, bj, bj + bcast_i(ny, src) - 1, lane, vis, W);
     }
 }
 
+// Conservative test of an axis-aligned box against the six frustum planes of M, in world
+// space.  For plane (row3 +- rowk) . (v, 1) >= 0 the largest value over the box is compared
+// with a negative margin proportional to the magnitude of the terms, so that rounding in this
+// test and in the per-vertex transform can never cull a box holding a vertex the exact rule
+// keeps.  NaNs compare false and therefore never cull.
+__device__ __forceinline__ bool box_outside_frustum(const float (&M)[16], float lx, float ly, float lz, float hx,
+                                                    float hy, float hz) {
+    const float eps = 1.52587890625e-05f;   // 2^-16
+    float ax = fmaxf(fabsf(lx), fabsf(hx)), ay = fmaxf(fabsf(ly), fabsf(hy)), az = fmaxf(fabsf(lz), fabsf(hz));
+    bool outside = false;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        const int r = (k < 2) ? 0 : (k < 4) ? 1 : 2;
+        float px, py, pz, pw, qx, qy, qz, qw;   // plane coefficients and their magnitudes
+        if (k == 4) {
+            px = M[8]; py = M[9]; pz = M[10]; pw = M[11];
+            qx = fabsf(px); qy = fabsf(py); qz = fabsf(pz); qw = fabsf(pw);
+        } else {
+            const float sg = (k == 0 || k == 2) ? 1.0f : -1.0f;
+            px = M[12] + sg * M[4 * r + 0]; py = M[13] + sg * M[4 * r + 1];
+            pz = M[14] + sg * M[4 * r + 2]; pw = M[15] + sg * M[4 * r + 3];
+            qx = fabsf(M[12]) + fabsf(M[4 * r + 0]); qy = fabsf(M[13]) + fabsf(M[4 * r + 1]);
+            qz = fabsf(M[14]) + fabsf(M[4 * r + 2]); qw = fabsf(M[15]) + fabsf(M[4 * r + 3]);
+        }
+        float dmax = pw + fmaxf(px * lx, px * hx) + fmaxf(py * ly, py * hy) + fmaxf(pz * lz, pz * hz);
+        float mag = fmaf(qx, ax, fmaf(qy, ay, fmaf(qz, az, qw)));
+        outside = outside || (dmax < -eps * mag);
+    }
+    return outside;
+}
 
 // One lane per queued straddling triangle: clip, project, fan, hand the pieces to emit().
 __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, int& small_count, const SceneDev& sc,
@@ -133,8 +174,8 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     bool have = lane < n;
     uint32_t ref = have ? L.clipq[first + lane] : 0u;
     uint32_t c = ref >> 7, slot = ref & 127u;
-    uint32_t t = sc.ctris[(size_t)c * 128 + slot] & 0x00FFFFFFu;
-    const float* cv = sc.cverts + (size_t)c * 192;
+    uint32_t t = gptr(sc.ctris)[(size_t)c * 128 + slot] & 0x00FFFFFFu;
+    const BPS_GLOBAL float* cv = gptr(sc.cverts) + (size_t)c * 192;
     Clip4 px[2][kMaxPoly];
     uint32_t oc_or = 0;
     for (int k = 0; k < 3; ++k) {
@@ -181,7 +222,7 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     bool ok = true;
     for (int i = 0; i < cnt; ++i) ok = project(px[cur][i], fp, pxy[i], piw[i]) && ok;
     if (!ok) cnt = 0;
-    const uint32_t* id_ptr = sc.ctri_id + (size_t)c * 128 + slot;
+    const BPS_GLOBAL uint32_t* id_ptr = gptr(sc.ctri_id) + (size_t)c * 128 + slot;
     for (int i = 1; ; ++i) {
         bool v = i + 1 < cnt;
         if (ballot64(v) == 0) break;
@@ -207,7 +248,7 @@ template <int NT>
 __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
-                                               uint32_t* __restrict__ out_id) {
+                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x;
@@ -218,9 +259,16 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     u64* vis = reinterpret_cast<u64*>(smem);
     unsigned char* wbase = smem + (size_t)HW * 8 + (size_t)wave * kWaveLdsBytes;
     WaveLds L;
-    L.stage = reinterpret_cast<float4*>(wbase);
-    L.smallq = reinterpret_cast<uint32_t*>(wbase + 64 * 16);
-    L.clipq = reinterpret_cast<uint32_t*>(wbase + 64 * 16 + 8 * 64 * 4);
+    L.stage = reinterpret_cast<float2*>(wbase);
+    L.stage_oc = reinterpret_cast<uint32_t*>(wbase + 64 * 8);
+    L.smallq = reinterpret_cast<uint32_t*>(wbase + 64 * 12);
+    L.clipq = reinterpret_cast<uint32_t*>(wbase + 64 * 12 + 8 * 64 * 4);
+
+    uint16_t* list = reinterpret_cast<uint16_t*>(smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes +
+                                                     (size_t)fp.round_blocks * 128);
+    uint32_t* list_count = counters;       // survivors appended in this round
+    uint32_t* pop_count = counters + 1;    // survivors handed out in this round
 
     const WorkItem item = items[blockIdx.x];
     const SceneDev sc = scenes[item.scene];
@@ -229,80 +277,150 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     for (int k = 0; k < 16; ++k) M[k] = view_proj[(size_t)item.env * 16 + k];
 
     for (int p = tid; p < HW; p += NT) vis[p] = kEmptyKey;
-    __syncthreads();
 
     int small_count = 0, clip_count = 0;
+    // diagnostics (only when the host passes a counter block): per-wave tallies, one atomic each at the end
+    uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0;
+    const unsigned long long t_start = stats ? wall_clock64() : 0ull;
     const uint32_t full_tri_mask = 0x00FFFFFFu;
+    const BPS_GLOBAL float* g_cverts = gptr(sc.cverts);
+    const BPS_GLOBAL uint32_t* g_ctris = gptr(sc.ctris);
+    const BPS_GLOBAL uint32_t* g_ctri_id = gptr(sc.ctri_id);
+    const BPS_GLOBAL float* g_bounds = gptr(sc.cbounds);
+    const uint32_t S = item.n_splits;
+    const uint32_t nblocks_total = (sc.n_clusters + 63u) / 64u;
+    const uint32_t nb_item = nblocks_total > item.split ? (nblocks_total - item.split + S - 1u) / S : 0u;
+    const uint32_t RB = (uint32_t)fp.round_blocks;
 
-    uint32_t c = item.c_begin + (uint32_t)wave;
-    // software prefetch of the next cluster's vertex and index words
-    float nx_ = 0, ny_ = 0, nz_ = 0;
-    uint32_t nt0 = 0, nt1 = 0;
-    if (c < item.c_end) {
-        const float* cv = sc.cverts + (size_t)c * 192;
-        nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
-        const uint32_t* ct = sc.ctris + (size_t)c * 128;
-        nt0 = ct[lane]; nt1 = ct[64 + lane];
-    }
-    for (;;) {
-        const bool have = c < item.c_end;
-        if (have) {
+    // The item's clusters are the 64-cluster blocks split, split + S, ... of its scene.  They are
+    // handled in rounds of RB blocks:
+    //   phase A  every lane tests one cluster's bounds against the frustum; survivors are appended
+    //            (ballot + prefix count, one LDS atomic per wavefront) to the work-group's list
+    //   phase B  wavefronts pop clusters from the list one at a time until it is empty
+    for (uint32_t rb = 0; rb < nb_item; rb += RB) {
+        if (tid == 0) { *list_count = 0u; *pop_count = 0u; }
+        __syncthreads();
+        const uint32_t rb_end = min(rb + RB, nb_item);
+        for (uint32_t jb = rb + (uint32_t)wave; jb < rb_end; jb += NW) {
+            const uint32_t cl = (jb * S + item.split) * 64u + (uint32_t)lane;
+            bool visible = cl < sc.n_clusters;
+            st_tested += (uint32_t)__popcll(ballot64(visible));
+            if (fp.cull) {
+                const uint32_t cc = visible ? cl : 0u;
+                float lx = g_bounds[cc], ly = g_bounds[sc.c_stride + cc], lz = g_bounds[2 * sc.c_stride + cc];
+                float hx = g_bounds[3 * sc.c_stride + cc], hy = g_bounds[4 * sc.c_stride + cc],
+                      hz = g_bounds[5 * sc.c_stride + cc];
+                visible = visible && !box_outside_frustum(M, lx, ly, lz, hx, hy, hz);
+            }
+            const u64 keep = ballot64(visible);
+            if (keep) {
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(list_count, (uint32_t)__popcll(keep));
+                base = __builtin_amdgcn_readfirstlane(base);
+                if (visible) list[base + rank_below(keep)] = (uint16_t)(((jb - rb) << 6) | (uint32_t)lane);
+            }
+        }
+        __syncthreads();
+        const uint32_t n_list = *list_count;
+        st_boxed += wave == 0 ? n_list : 0u;
+
+        // pop one ahead so that the next cluster's words are in flight while this one is processed
+        uint32_t pop = 0;
+        if (lane == 0) pop = atomicAdd(pop_count, 1u);
+        pop = __builtin_amdgcn_readfirstlane(pop);
+        float nx_ = 0, ny_ = 0, nz_ = 0;
+        uint32_t nt0 = 0, nt1 = 0, c_next = 0;
+        if (pop < n_list) {
+            const uint32_t e = list[pop];
+            c_next = ((rb + (e >> 6)) * S + item.split) * 64u + (e & 63u);
+            const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
+            nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
+            const BPS_GLOBAL uint32_t* ct = g_ctris + (size_t)c_next * 128;
+            nt0 = ct[lane]; nt1 = ct[64 + lane];
+        }
+        while (pop < n_list) {
+            const uint32_t c = c_next;
             float x = nx_, y = ny_, z = nz_;
             uint32_t t0 = nt0, t1 = nt1;
-            uint32_t cn = c + NW;
-            if (cn < item.c_end) {
-                const float* cv = sc.cverts + (size_t)cn * 192;
+            if (lane == 0) pop = atomicAdd(pop_count, 1u);
+            pop = __builtin_amdgcn_readfirstlane(pop);
+            if (pop < n_list) {
+                const uint32_t e = list[pop];
+                c_next = ((rb + (e >> 6)) * S + item.split) * 64u + (e & 63u);
+                const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
                 nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
-                const uint32_t* ct = sc.ctris + (size_t)cn * 128;
+                const BPS_GLOBAL uint32_t* ct = g_ctris + (size_t)c_next * 128;
                 nt0 = ct[lane]; nt1 = ct[64 + lane];
             }
 
             // ---- vertex phase
-            Clip4 cl = to_clip(M, x, y, z);
-            uint32_t oc = outcode(cl);
-            bool culled = false;
-#pragma unroll
-            for (int k = 0; k < 6; ++k) culled = culled || (ballot64((oc >> k) & 1u) == ~0ull);
-            if (!culled) {
-                uint32_t xy;
-                float iw;
-                bool ok = project(cl, fp, xy, iw);
-                if (oc == 0 && !ok) oc = kInvalid;
-                wave_lds_sync();   // earlier reads of the stage are done
-                L.stage[lane] = make_float4(__uint_as_float(xy), iw, __uint_as_float(oc), 0.0f);
-                wave_lds_sync();
-
-                // ---- triangle phase: two slots per lane
-                const int ntri = __builtin_amdgcn_readfirstlane((int)(t0 >> 24));
-#pragma unroll 1
-                for (int slot = 0; slot < 2; ++slot) {
-                    if (slot == 1 && ntri <= 64) break;
-                    uint32_t t = (slot == 0 ? t0 : t1) & full_tri_mask;
-                    float4 a = L.stage[t & 0xFFu], b = L.stage[(t >> 8) & 0xFFu], d = L.stage[t >> 16];
-                    uint32_t oa = __float_as_uint(a.z), ob = __float_as_uint(b.z), od = __float_as_uint(d.z);
-                    uint32_t o_or = oa | ob | od, o_and = oa & ob & od;
-                    bool live = ((o_or & kInvalid) == 0) && (o_and == 0) && (slot * 64 + lane < ntri);
-                    bool fast = live && o_or == 0;
-                    bool straddle = live && o_or != 0;
-                    push_clip(L, clip_count, straddle, (c << 7) | (uint32_t)(slot * 64 + lane));
-                    emit(L, small_count, fast, __float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), a.y, b.y,
-                         d.y, sc.ctri_id + (size_t)c * 128 + slot * 64 + lane, lane, vis, fp.H, fp.W);
-                }
-            }
-            c += NW;
-        }
-        // ---- clip queue: full wavefronts while streaming, the remainder at the end
-        while (clip_count >= 64 || (!have && clip_count > 0)) {
-            int n = clip_count < 64 ? clip_count : 64;
+            Clip4 cp = to_clip(M, x, y, z);
+            bool o0 = !(cp.w + cp.x >= 0.0f), o1 = !(cp.w - cp.x >= 0.0f);
+            bool o2 = !(cp.w + cp.y >= 0.0f), o3 = !(cp.w - cp.y >= 0.0f);
+            bool o4 = !(cp.z >= 0.0f), o5 = !(cp.w - cp.z >= 0.0f);
+            bool culled = ballot64(o0) == ~0ull || ballot64(o1) == ~0ull || ballot64(o2) == ~0ull ||
+                          ballot64(o3) == ~0ull || ballot64(o4) == ~0ull || ballot64(o5) == ~0ull;
+            if (culled) continue;
+            ++st_drawn;
+            uint32_t oc = (o0 ? 1u : 0u) | (o1 ? 2u : 0u) | (o2 ? 4u : 0u) | (o3 ? 8u : 0u) | (o4 ? 16u : 0u) |
+                          (o5 ? 32u : 0u);
+            if (!all_finite(cp)) oc |= kInvalid;
+            uint32_t xy;
+            float iw;
+            bool ok = project(cp, fp, xy, iw);
+            if (oc == 0 && !ok) oc = kInvalid;
+            const bool all_inside = ballot64(oc != 0) == 0;
+            wave_lds_sync();   // earlier reads of the stage are done
+            L.stage[lane] = make_float2(__uint_as_float(xy), iw);
+            if (!all_inside) L.stage_oc[lane] = oc;
             wave_lds_sync();
-            drain_clip(L, clip_count - n, n, small_count, sc, M, fp, lane, vis);
-            clip_count -= n;
+
+            // ---- triangle phase: two slots per lane
+            const int ntri = __builtin_amdgcn_readfirstlane((int)(t0 >> 24));
+#pragma unroll 1
+            for (int slot = 0; slot < 2; ++slot) {
+                if (slot == 1 && ntri <= 64) break;
+                uint32_t t = (slot == 0 ? t0 : t1) & full_tri_mask;
+                const uint32_t i0 = t & 0xFFu, i1 = (t >> 8) & 0xFFu, i2 = t >> 16;
+                float2 a = L.stage[i0], b = L.stage[i1], d = L.stage[i2];
+                bool fast = slot * 64 + lane < ntri;
+                if (!all_inside) {
+                    uint32_t oa = L.stage_oc[i0], ob = L.stage_oc[i1], od = L.stage_oc[i2];
+                    uint32_t o_or = oa | ob | od, o_and = oa & ob & od;
+                    bool live = fast && ((o_or & kInvalid) == 0) && (o_and == 0);
+                    fast = live && o_or == 0;
+                    st_straddle += (uint32_t)__popcll(ballot64(live && o_or != 0));
+                    push_clip(L, clip_count, live && o_or != 0, (c << 7) | (uint32_t)(slot * 64 + lane));
+                }
+                emit(L, small_count, fast, __float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), a.y, b.y,
+                     d.y, g_ctri_id + (size_t)c * 128 + slot * 64 + lane, lane, vis, fp.H, fp.W);
+            }
+            // ---- clip queue: full wavefronts only while streaming
+            while (clip_count >= 64) {
+                wave_lds_sync();
+                drain_clip(L, clip_count - 64, 64, small_count, sc, M, fp, lane, vis);
+                clip_count -= 64;
+            }
         }
-        if (!have) break;
+        __syncthreads();
+    }
+    if (clip_count > 0) {
+        wave_lds_sync();
+        drain_clip(L, 0, clip_count, small_count, sc, M, fp, lane, vis);
     }
     if (small_count > 0) {
         wave_lds_sync();
         drain_small(L, small_count, lane, vis, fp.W);
+    }
+    if (stats && lane == 0) {
+        atomicAdd(&stats[0], (unsigned long long)st_tested);
+        atomicAdd(&stats[1], (unsigned long long)st_boxed);
+        atomicAdd(&stats[2], (unsigned long long)st_drawn);
+        atomicAdd(&stats[3], (unsigned long long)st_straddle);
+        unsigned long long dt = wall_clock64() - t_start;
+        atomicAdd(&stats[4], dt);
+        atomicMax(&stats[5], dt);
+        if (wave == 0) stats[8 + blockIdx.x] = dt;      // duration of this work-group's first wave
     }
     __syncthreads();
 
@@ -336,6 +454,11 @@ __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float
     if (hit) gvis[p] = kEmptyKey;
 }
 
+__global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
 __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n) {
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p < n) gvis[p] = kEmptyKey;
@@ -350,13 +473,13 @@ hipError_t prepare_raster(int threads, size_t lds) {
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
-                   uint32_t* out_id) {
+                   uint32_t* out_id, unsigned long long* stats) {
     if (threads == 256)
-        hipLaunchKernelGGL(k_raster<256>, grid, dim3(256), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id);
+        hipLaunchKernelGGL(k_raster<256>, grid, dim3(256), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
     else if (threads == 512)
-        hipLaunchKernelGGL(k_raster<512>, grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id);
+        hipLaunchKernelGGL(k_raster<512>, grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
     else
-        hipLaunchKernelGGL(k_raster<1024>, grid, dim3(1024), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id);
+        hipLaunchKernelGGL(k_raster<1024>, grid, dim3(1024), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
 }
 
 }  // namespace bps

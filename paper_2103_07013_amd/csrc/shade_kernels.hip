@@ -30,7 +30,7 @@ __device__ __forceinline__ bool piece_colour(const SVert& v0, const SVert& v1, c
     const SVert& a = v0;
     const SVert& b = s.swapped ? v2 : v1;
     const SVert& c = s.swapped ? v1 : v2;
-    int px = (i << 8) + 128 + kBias, py = (j << 8) + 128 + kBias;
+    int px = (i << 8) + 128 - kOrigin, py = (j << 8) + 128 - kOrigin;
     int E0 = __mul24(s.dx0, py - s.Y1) - __mul24(s.dy0, px - s.X1);
     int E1 = __mul24(s.dx1, py - s.Y2) - __mul24(s.dy1, px - s.X2);
     int E2 = __mul24(s.dx2, py - s.Y0) - __mul24(s.dy2, px - s.X0);

@@ -8,12 +8,13 @@ pytestmark = pytest.mark.gpu
 NOHIT = 0xFFFFFFFF
 
 
-def _render_gpu(scenes, scene_ids, view_proj, H, W, splits=0, threads=0, background=0.0, device_matrices=False):
+def _render_gpu(scenes, scene_ids, view_proj, H, W, splits=0, threads=0, background=0.0, device_matrices=False,
+                flags=0):
     import torch
     import paper_2103_07013_amd as bps
     B = len(scene_ids)
     with bps.Renderer(max_batch=B, height=H, width=W, splits=splits, threads=threads,
-                      background_depth=background) as r:
+                      background_depth=background, flags=flags) as r:
         handles = [r.load_scene(s.vertices, s.indices, s.colors) for s in scenes]
         ids = np.array([handles[k] for k in scene_ids], np.int32)
         vp = torch.from_numpy(np.ascontiguousarray(view_proj)).cuda() if device_matrices else view_proj
@@ -63,6 +64,24 @@ def test_mixed_scenes_interleaved_ids():
     ref = _oracle(w)
     gd, gi, _ = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, device_matrices=True)
     _compare(gd, gi, ref, "mixed")
+
+
+def test_cluster_culling_never_changes_a_frame():
+    import paper_2103_07013_amd as bps
+    w = synth.build_config(2, B=32)
+    ref = _oracle(w)
+    a = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W)
+    b = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, flags=bps.FLAG_NO_CLUSTER_CULL)
+    _compare(a[0], a[1], ref, "culling on")
+    _compare(b[0], b[1], ref, "culling off")
+    # cameras with pitch and roll-free tilt, close to walls: bounds straddle every plane
+    Ms = np.stack([synth.view_proj_from_pose((1.0 + 1.1 * k, 0.3 + 0.1 * k, 0.7 * k + 0.4), 0.8 * k, 0.3 * (k % 5 - 2))
+                   for k in range(16)])
+    import oracle
+    s = w.scenes[0]
+    ref2 = oracle.render_scene(s.vertices, s.indices, Ms, 64, 64)
+    c = _render_gpu(w.scenes, [0] * 16, Ms, 64, 64)
+    _compare(c[0], c[1], ref2, "tilted cameras")
 
 
 def test_random_soup_with_heavy_clipping():
