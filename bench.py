@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--no-cull", action="store_true", help="stream every cluster (no frustum culling of clusters)")
+    ap.add_argument("--no-occlusion", action="store_true", help="frustum culling of clusters only")
     ap.add_argument("--cpu-envs", type=int, default=512, help="environments in the oracle timing sample (0 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of rendering, run a plain device-to-device copy of this many MiB five times "
@@ -84,7 +85,8 @@ def main():
     if w.rgbd:
         sys.exit("bench.py: RGB-D workloads are not wired into the benchmark yet")
     r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, splits=args.splits, threads=args.threads,
-                     flags=bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0)
+                     flags=(bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0) |
+                           (bps.FLAG_NO_OCCLUSION_CULL if args.no_occlusion else 0))
     handles = [r.load_scene(s.vertices, s.indices, None) for s in w.scenes]
     ids = np.array([handles[k] for k in w.scene_ids], np.int32)
     vp = torch.from_numpy(w.view_proj).cuda()

@@ -45,7 +45,10 @@ enum { BPS_MODE_DEPTH = 0, BPS_MODE_RGBD = 1 };
 
 /* bps_config.flags.  Cluster culling is the paper's frustum culling of geometry chunks
  * (Sec. 3.2 "Pipelined geometry culling"); it never changes a frame, only the work done. */
-enum { BPS_FLAG_NO_CLUSTER_CULL = 1 };
+enum {
+    BPS_FLAG_NO_CLUSTER_CULL = 1,   /* stream every cluster of the scene for every environment */
+    BPS_FLAG_NO_OCCLUSION_CULL = 2  /* frustum culling only: do not skip clusters hidden behind nearer geometry */
+};
 
 typedef struct {
     int32_t device;          /* HIP device ordinal */
@@ -54,7 +57,7 @@ typedef struct {
     int32_t mode;            /* BPS_MODE_DEPTH or BPS_MODE_RGBD */
     float background_depth;  /* written where no triangle covers the pixel centre */
     int32_t splits;          /* work-groups per environment; 0 = choose from B and the device */
-    int32_t threads;         /* work-group size: 0 = default, else 256, 512 or 1024 */
+    int32_t threads;         /* work-group size: 0 = default, else 256, 384, 512 or 1024 */
     uint32_t flags;          /* BPS_FLAG_* bits, 0 = defaults */
 } bps_config;
 
@@ -112,12 +115,15 @@ bps_status bps_set_profiling(bps_renderer *r, int32_t enable);
 bps_status bps_last_kernel_ms(bps_renderer *r, float *ms);
 bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total_ms);
 
-/* Diagnostics: when enabled, the raster kernel tallies its work into a device block that
- * bps_read_diagnostics copies out after waiting for the device:
- *   out[0] clusters whose bounds were tested       out[1] clusters that passed the bounds test
- *   out[2] clusters that reached the triangle phase out[3] triangles sent to the clipper
- *   out[4] sum and out[5] maximum over wavefronts of their run time in 100 MHz ticks
- *   out[8 + g] run time of work-group g's first wavefront.
+/* Diagnostics: when enabled (1), the raster kernel tallies its work into a device block that
+ * bps_read_diagnostics copies out after waiting for the device: 16 words per work-group g,
+ *   out[16 g + 0] clusters whose bounds were tested      [1] clusters that passed the bounds tests
+ *   [2] clusters that reached the triangle phase           [3] triangles sent to the clipper
+ *   [4] clusters skipped because nearer geometry already covered their footprint
+ *   [5] run time of the group's slowest wavefront, [15] of its first, in 100 MHz ticks
+ *   [6..13] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
+ *           in the set-up, bounds testing, barrier, depth sort, (unused), cluster processing,
+ *           barrier and flush phases.
  * `capacity` is the room in `out` (in words), *written the number of words copied. */
 bps_status bps_set_diagnostics(bps_renderer *r, int32_t enable);
 bps_status bps_read_diagnostics(bps_renderer *r, uint64_t *out, uint32_t capacity, uint32_t *written);

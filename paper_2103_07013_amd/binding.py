@@ -10,6 +10,7 @@ from . import build as _build
 
 MODE_DEPTH, MODE_RGBD = 0, 1
 FLAG_NO_CLUSTER_CULL = 1
+FLAG_NO_OCCLUSION_CULL = 2
 EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
            "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 
@@ -182,8 +183,8 @@ def bps_kernel_ms_total(handle):
     return int(n.value), float(ms.value)
 
 
-def bps_set_diagnostics(handle, enable=True):
-    _check(load_library().bps_set_diagnostics(handle, 1 if enable else 0), handle)
+def bps_set_diagnostics(handle, enable=1):
+    _check(load_library().bps_set_diagnostics(handle, int(enable)), handle)
 
 
 def bps_read_diagnostics(handle, capacity=1 << 16):

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -27,7 +28,7 @@ thread_local std::string g_create_error = "";
 struct HostScene {
     bool live = false;
     bps::SceneDev dev{};
-    void* allocs[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    void* allocs[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     uint64_t bytes = 0;
     bool has_colors = false;
 };
@@ -47,7 +48,8 @@ struct bps_renderer {
     int device = 0;
     int num_cu = 0;
     int threads = 512;
-    int round_blocks = 32;
+    int list_cap = 2048;
+    int round_target = 64;
     size_t lds = 0;
     size_t max_lds = 0;
     std::string error = "";
@@ -59,7 +61,7 @@ struct bps_renderer {
     uint32_t* ids = nullptr;              // [max_batch][H][W], RGB-D requests without a caller id buffer
     unsigned long long* d_stats = nullptr;   // diagnostics block: 8 counters + one duration per work-group
     size_t stats_cap = 0;
-    bool want_stats = false;
+    bool want_stats = false, want_phase_timers = false;
     std::vector<hipEvent_t> ev;           // profiling: pairs (start, stop), one pair per request
     size_t ev_used = 0;
     bool profiling = false;
@@ -124,10 +126,10 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: height and width must be multiples of 8 in 8..128");
     if (cfg->mode != BPS_MODE_DEPTH && cfg->mode != BPS_MODE_RGBD)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown mode %d", cfg->mode);
-    if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 512 && cfg->threads != 1024)
-        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 512 or 1024");
+    if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 384 && cfg->threads != 512 && cfg->threads != 1024)
+        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 384, 512 or 1024");
     if (cfg->splits < 0) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be >= 0");
-    if (cfg->flags & ~(uint32_t)BPS_FLAG_NO_CLUSTER_CULL) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
+    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
         return fail(nullptr, BPS_ERR_HIP, "bps_create: no HIP device available (this library has no CPU path)");
@@ -153,24 +155,31 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         if (hipDeviceGetAttribute(&lds_optin, hipDeviceAttributeSharedMemPerBlockOptin, r->device) != hipSuccess) lds_optin = 0;
         (void)hipGetLastError();
         r->max_lds = std::max<size_t>(prop.sharedMemPerBlock, (size_t)std::max(lds_optin, 0));
-        // preferred work-group size whose LDS footprint fits, with the longest survivor list that fits
-        const int order[3] = {512, 256, 1024};
-        const int rounds[3] = {32, 16, 8};
+        // preferred work-group size whose LDS footprint leaves room for a useful survivor list
+        const int order[4] = {512, 384, 256, 1024};
         r->threads = 0;
-        for (int rb : rounds) {
-            if (cfg->threads) {
-                if (bps::lds_bytes(cfg->height, cfg->width, cfg->threads, rb) <= r->max_lds) r->threads = cfg->threads;
-            } else {
-                for (int t : order)
-                    if (bps::lds_bytes(cfg->height, cfg->width, t, rb) <= r->max_lds) { r->threads = t; break; }
-            }
-            if (r->threads) { r->round_blocks = rb; break; }
+        auto fit_cap = [&](int t) -> int {
+            size_t fixed = bps::lds_bytes(cfg->height, cfg->width, t, 0);
+            if (fixed >= r->max_lds) return 0;
+            // two work-groups per compute unit when the frame allows it
+            size_t budget = fixed * 2 + 2 * 12 * 512 <= r->max_lds ? r->max_lds / 2 : r->max_lds;
+            size_t cap = std::min<size_t>(2048, (budget - fixed) / 12);
+            return (int)(cap & ~(size_t)63);
+        };
+        if (cfg->threads) {
+            if (fit_cap(cfg->threads) >= 128) r->threads = cfg->threads;
+        } else {
+            for (int t : order)
+                if (fit_cap(t) >= 512) { r->threads = t; break; }
         }
         if (!r->threads)
             return fail(r, BPS_ERR_UNSUPPORTED, "bps_create: a %dx%d frame needs %zu bytes of LDS, device offers %zu",
-                        cfg->height, cfg->width, bps::lds_bytes(cfg->height, cfg->width, cfg->threads ? cfg->threads : 256, 8),
+                        cfg->height, cfg->width, bps::lds_bytes(cfg->height, cfg->width, cfg->threads ? cfg->threads : 256, 512),
                         r->max_lds);
-        r->lds = bps::lds_bytes(cfg->height, cfg->width, r->threads, r->round_blocks);
+        r->list_cap = fit_cap(r->threads);
+        r->round_target = r->list_cap / 2;
+        if (const char* e = std::getenv("BPS_ROUND_TARGET")) r->round_target = std::max(1, std::atoi(e));   // tuning knob
+        r->lds = bps::lds_bytes(cfg->height, cfg->width, r->threads, r->list_cap);
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
         BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
@@ -226,7 +235,7 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
     } catch (const std::bad_alloc&) {
         return fail(r, BPS_ERR_OOM, "bps_load_scene: out of host memory while clustering");
     }
-    if (cs.count == 0 || cs.count >= (1u << 25)) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: unsupported cluster count %u", cs.count);
+    if (cs.count == 0 || cs.count >= (1u << 24)) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: unsupported cluster count %u", cs.count);
 
     BPS_HIP(r, hipSetDevice(r->device));
     HostScene hs;
@@ -262,6 +271,19 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
         if ((st = upload(6, planes.data(), planes.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
         hs.dev.cbounds = (const float*)p;
         hs.dev.c_stride = stride;
+        // bounds of each block of 64 consecutive clusters (the unit that is depth-sorted per environment)
+        const uint32_t nblocks = stride / 64u;
+        std::vector<float> bplanes((size_t)6 * nblocks);
+        for (uint32_t b = 0; b < nblocks; ++b)
+            for (int a = 0; a < 6; ++a) {
+                float v = cs.bounds[(size_t)b * 64 * 6 + a];
+                for (uint32_t c = b * 64; c < std::min(cs.count, b * 64 + 64); ++c)
+                    v = a < 3 ? std::min(v, cs.bounds[(size_t)c * 6 + a]) : std::max(v, cs.bounds[(size_t)c * 6 + a]);
+                bplanes[(size_t)a * nblocks + b] = v;
+            }
+        if ((st = upload(7, bplanes.data(), bplanes.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
+        hs.dev.bbounds = (const float*)p;
+        hs.dev.b_stride = nblocks;
     }
     hs.dev.n_clusters = cs.count;
     hs.dev.n_tris = T;
@@ -429,20 +451,22 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     fp.ymax = 2.0f * fp.sy + 64.0f;
     fp.background = r->cfg.background_depth;
     fp.merge = S > 1 ? 1 : 0;
-    fp.cull = (r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL) ? 0 : 1;
-    fp.round_blocks = r->round_blocks;
+    fp.cull = (r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL) ? 0 : (r->cfg.flags & BPS_FLAG_NO_OCCLUSION_CULL) ? 1 : 2;
+    fp.list_cap = r->list_cap;
+    fp.round_target = r->round_target;
+    fp.phase_timers = (r->want_stats && r->want_phase_timers) ? 1 : 0;
 
     unsigned long long* d_stats = nullptr;
     if (r->want_stats) {
-        if (r->stats_cap < 8 + n_items) {
+        if (r->stats_cap < 16 * n_items) {
             if (r->d_stats) (void)hipFree(r->d_stats);
             r->d_stats = nullptr;
             r->stats_cap = 0;
-            BPS_HIP(r, hipMalloc((void**)&r->d_stats, (8 + n_items) * sizeof(unsigned long long)));
-            r->stats_cap = 8 + n_items;
+            BPS_HIP(r, hipMalloc((void**)&r->d_stats, (16 * n_items) * sizeof(unsigned long long)));
+            r->stats_cap = 16 * n_items;
         }
-        hipLaunchKernelGGL(bps::k_zero_words, dim3((unsigned)((8 + n_items + 255) / 256)), dim3(256), 0, stream, r->d_stats,
-                           8 + n_items);
+        hipLaunchKernelGGL(bps::k_zero_words, dim3((unsigned)((16 * n_items + 255) / 256)), dim3(256), 0, stream, r->d_stats,
+                           16 * n_items);
         d_stats = r->d_stats;
     }
     hipEvent_t ev_stop = nullptr;
@@ -510,6 +534,7 @@ bps_status bps_kernel_ms_total(bps_renderer* r, uint32_t* launches, float* total
 bps_status bps_set_diagnostics(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
     r->want_stats = enable != 0;
+    r->want_phase_timers = enable > 1;
     return BPS_OK;
 }
 
@@ -518,7 +543,7 @@ bps_status bps_read_diagnostics(bps_renderer* r, uint64_t* out, uint32_t capacit
     if (!r->d_stats) return fail(r, BPS_ERR_INVALID_ARG, "bps_read_diagnostics: no request ran with diagnostics enabled");
     BPS_HIP(r, hipSetDevice(r->device));
     BPS_HIP(r, hipDeviceSynchronize());
-    size_t n = std::min<size_t>(capacity, 8 + (size_t)r->last_groups);
+    size_t n = std::min<size_t>(capacity, 16 * (size_t)r->last_groups);
     BPS_HIP(r, hipMemcpy(out, r->d_stats, n * sizeof(uint64_t), hipMemcpyDeviceToHost));
     *written = (uint32_t)n;
     return BPS_OK;

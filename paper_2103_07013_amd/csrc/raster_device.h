@@ -142,13 +142,20 @@ __device__ __forceinline__ uint32_t outcode(const Clip4& c) {
     return oc;
 }
 
-// Perspective divide + snap.  Returns false when the vertex cannot be placed on the sub-pixel grid.
-__device__ __forceinline__ bool project(const Clip4& c, const FrameParams& fp, uint32_t& xy, float& iw) {
+// Perspective divide + snap.  Returns false when the vertex cannot be placed on the sub-pixel grid
+// of the frame (the numeric rule then drops its triangle).  can_project tells whether the vertex is
+// in front of the eye with finite screen coordinates; such a vertex outside the frame is packed
+// with its coordinates clamped to the 16-bit range, which keeps it on its side of the frame.
+__device__ __forceinline__ bool project(const Clip4& c, const FrameParams& fp, uint32_t& xy, float& iw,
+                                        bool& can_project) {
     iw = 1.0f / c.w;
     float xn = c.x * iw, yn = c.y * iw;
     float fx = fmaf(xn, fp.sx, fp.sx), fy = fmaf(yn, fp.sy, fp.sy);
     bool ok = (c.w > 0.0f) && fx >= -64.0f && fx <= fp.xmax && fy >= -64.0f && fy <= fp.ymax;
-    xy = pack_xy(__float2int_rn(fx), __float2int_rn(fy));
+    can_project = (c.w > 0.0f) && fabsf(fx) < 3.0e38f && fabsf(fy) < 3.0e38f;
+    int X = min(max(__float2int_rn(fx), kOrigin - 32768), kOrigin + 32767);
+    int Y = min(max(__float2int_rn(fy), kOrigin - 32768), kOrigin + 32767);
+    xy = pack_xy(X, Y);
     return ok;
 }
 

@@ -27,10 +27,11 @@ struct SceneDev {
     const uint32_t* ctris;     // [C][128]   packed local indices, count in bits 24..31 of word 0
     const uint32_t* ctri_id;   // [C][128]   original triangle row
     const float* cbounds;      // [6][c_stride] cluster bounds: min x, y, z then max x, y, z
+    const float* bbounds;      // [6][b_stride] bounds of each block of 64 consecutive clusters
     const float* verts;        // [V][3]     original arrays, used when shading
     const uint32_t* indices;   // [T][3]
     const uint8_t* colors;     // [V][3] or null
-    uint32_t n_clusters, n_tris, n_verts, c_stride;
+    uint32_t n_clusters, n_tris, n_verts, c_stride, b_stride, pad;
 };
 
 // One work-group's share: environment `env`, and of its scene the 64-cluster blocks
@@ -45,22 +46,30 @@ struct FrameParams {
     float xmax, ymax;      // 2*sx + 64, 2*sy + 64
     float background;
     int32_t merge;         // 0: resolve straight to the output; 1: atomic-min into the global buffer
-    int32_t cull;          // 1: skip clusters whose bounds lie outside one frustum plane
-    int32_t round_blocks;  // 64-cluster blocks tested per round (capacity of the survivor list / 64)
+    int32_t cull;          // 0: stream every cluster; 1: frustum-cull clusters; 2: frustum + occlusion cull
+    int32_t list_cap;      // capacity of the work-group's survivor list, in clusters
+    int32_t round_target;  // survivors queued before a round's testing stops
+    int32_t phase_timers;  // diagnostics: also time the kernel's phases (slows it down)
 };
 
 constexpr unsigned long long kEmptyKey = ~0ull;
 constexpr int kOrigin = 16384;         // packed screen coordinates are stored relative to pixel 64
 constexpr int kSmallMax = 4;           // pixel centres a "small" triangle may touch
 constexpr uint32_t kInvalid = 0x40u;   // outcode bit: vertex unusable, drop its triangles
+constexpr uint32_t kNoProject = 0x80u; // outcode bit: vertex has no finite screen position (w <= 0 or overflow)
 
 // per-wave LDS block: 64 staged vertices (8 B + 4 B outcode each), small queue 8 x 64 words,
 // clip queue 192 words
 constexpr uint32_t kWaveLdsBytes = 64 * 12 + 8 * 64 * 4 + 192 * 4;
 
-// visibility buffer, per-wave blocks, survivor list (2 B per cluster of a round), two counters
-__host__ __device__ inline size_t lds_bytes(int H, int W, int threads, int round_blocks) {
-    return (size_t)H * W * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)round_blocks * 128 + 16;
+constexpr int kOrderCap = 1024;        // blocks of one item that can be depth-sorted
+constexpr int kDepthBins = 128;        // bins of the per-round depth sort of surviving clusters
+
+// visibility buffer, per-wave blocks, survivor list (8 B record + two 2 B sort words per cluster),
+// block order, depth histogram and its prefix, four counters
+__host__ __device__ inline size_t lds_bytes(int H, int W, int threads, int list_cap) {
+    return (size_t)H * W * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)list_cap * 12 + kOrderCap * 2 +
+           2 * kDepthBins * 4 + 32;
 }
 
 template <int NT>

@@ -23,12 +23,17 @@ struct WaveLds {
 };
 
 // One lane per queued small triangle: at most kSmallMax pixel centres each.
-__device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u64* vis, int W) {
+__device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u64* vis, int W,
+                                            const BPS_GLOBAL uint32_t* ctri_id) {
     bool have = lane < n;
+    // the queue holds the triangle's slot in the cluster arrays; its id is fetched here, one
+    // gather per 64 triangles, and arrives while the edge set-up is computed
+    const uint32_t ref = have ? L.smallq[6 * 64 + lane] : 0u;
+    const uint32_t id = ctri_id[ref];
     uint32_t xy0 = L.smallq[0 * 64 + lane], xy1 = L.smallq[1 * 64 + lane], xy2 = L.smallq[2 * 64 + lane];
     float iw0 = __uint_as_float(L.smallq[3 * 64 + lane]), iw1 = __uint_as_float(L.smallq[4 * 64 + lane]),
           iw2 = __uint_as_float(L.smallq[5 * 64 + lane]);
-    uint32_t id = L.smallq[6 * 64 + lane], box = L.smallq[7 * 64 + lane];
+    uint32_t box = L.smallq[7 * 64 + lane];
     Setup s = make_setup(xy0, xy1, xy2, iw0, iw1, iw2);
     int i_lo = (int)(box & 0xFFu), j_lo = (int)((box >> 8) & 0xFFu);
     int nx = (int)((box >> 16) & 0xFFu), ny = (int)(box >> 24);
@@ -45,8 +50,8 @@ __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u
 
 // Append small triangles to the wave's queue; whenever it reaches 64 entries, drain them.
 __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool want, uint32_t xy0, uint32_t xy1,
-                                           uint32_t xy2, float iw0, float iw1, float iw2, uint32_t id, uint32_t box,
-                                           int lane, u64* vis, int W) {
+                                           uint32_t xy2, float iw0, float iw1, float iw2, uint32_t ref, uint32_t box,
+                                           int lane, u64* vis, int W, const BPS_GLOBAL uint32_t* ctri_id) {
     u64 mask = ballot64(want);
     if (mask == 0) return;
     int n = __popcll(mask);
@@ -59,18 +64,18 @@ __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool wa
         L.smallq[0 * 64 + pos] = xy0; L.smallq[1 * 64 + pos] = xy1; L.smallq[2 * 64 + pos] = xy2;
         L.smallq[3 * 64 + pos] = __float_as_uint(iw0); L.smallq[4 * 64 + pos] = __float_as_uint(iw1);
         L.smallq[5 * 64 + pos] = __float_as_uint(iw2);
-        L.smallq[6 * 64 + pos] = id; L.smallq[7 * 64 + pos] = box;
+        L.smallq[6 * 64 + pos] = ref; L.smallq[7 * 64 + pos] = box;
     }
     if (n >= room) {
         wave_lds_sync();
-        drain_small(L, 64, lane, vis, W);
+        drain_small(L, 64, lane, vis, W, ctri_id);
         wave_lds_sync();
         pos -= 64;
         if (later) {
             L.smallq[0 * 64 + pos] = xy0; L.smallq[1 * 64 + pos] = xy1; L.smallq[2 * 64 + pos] = xy2;
             L.smallq[3 * 64 + pos] = __float_as_uint(iw0); L.smallq[4 * 64 + pos] = __float_as_uint(iw1);
             L.smallq[5 * 64 + pos] = __float_as_uint(iw2);
-            L.smallq[6 * 64 + pos] = id; L.smallq[7 * 64 + pos] = box;
+            L.smallq[6 * 64 + pos] = ref; L.smallq[7 * 64 + pos] = box;
         }
         count = n - room;
     } else {
@@ -99,34 +104,41 @@ typedef short short2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ short2v as_s2(uint32_t v) { return __builtin_bit_cast(short2v, v); }
 __device__ __forceinline__ uint32_t as_u32(short2v v) { return __builtin_bit_cast(uint32_t, v); }
 
-// Bounding-box cull, classification and hand-off of one candidate triangle per lane.
-// Works on both axes at once with packed 16-bit arithmetic.  Pixel i has its centre at
-// 256 (i - 64) + 128 in packed coordinates, so the first centre at or right of x is
-// (x + 127) >> 8 and the last centre at or left of x is (x - 128) >> 8 (both minus 64).
-// id_ptr is only dereferenced by lanes whose triangle can touch a pixel centre.
-__device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool valid, uint32_t xy0, uint32_t xy1,
-                                     uint32_t xy2, float iw0, float iw1, float iw2, const BPS_GLOBAL uint32_t* id_ptr,
-                                     int lane, u64* vis, int H, int W) {
+// Pixel centres inside a triangle's bounding box, both axes at once with packed 16-bit
+// arithmetic.  Pixel i has its centre at 256 (i - 64) + 128 in packed coordinates, so the first
+// centre at or right of x is (x + 127) >> 8 and the last centre at or left of x is (x - 128) >> 8
+// (both minus 64).  Returns false when the box, clamped to the frame, holds no centre; otherwise
+// lo = first pixel - 64 and ext = last - first per axis.
+__device__ __forceinline__ bool centre_box(uint32_t xy0, uint32_t xy1, uint32_t xy2, int H, int W, short2v& lo,
+                                           short2v& ext) {
     short2v a = as_s2(xy0), b = as_s2(xy1), c = as_s2(xy2);
     short2v mn = __builtin_elementwise_min(a, __builtin_elementwise_min(b, c));
     short2v mx = __builtin_elementwise_max(a, __builtin_elementwise_max(b, c));
-    short2v lo = (mn + (short)127) >> (short)8;
+    lo = (mn + (short)127) >> (short)8;
     short2v hi = (mx - (short)128) >> (short)8;
     short2v lo_clamp = {(short)-64, (short)-64};
     short2v hi_clamp = {(short)(W - 65), (short)(H - 65)};
     lo = __builtin_elementwise_max(lo, lo_clamp);
     hi = __builtin_elementwise_min(hi, hi_clamp);
-    short2v ext = hi - lo;                              // both halves >= 0: some pixel centre is inside
-    valid = valid && (as_u32(ext) & 0x80008000u) == 0;
+    ext = hi - lo;                              // both halves >= 0: some pixel centre is inside
+    return (as_u32(ext) & 0x80008000u) == 0;
+}
+
+// Classification and hand-off of one candidate triangle per lane whose box holds a pixel centre.
+// ref = cluster * 128 + slot addresses the triangle's original id in ctri_id; small triangles
+// carry it through the queue, only large ones look the id up here.
+__device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool valid, short2v lo, short2v ext,
+                                     uint32_t xy0, uint32_t xy1, uint32_t xy2, float iw0, float iw1, float iw2,
+                                     uint32_t ref, const BPS_GLOBAL uint32_t* ctri_id, int lane, u64* vis, int W) {
     u64 vmask = ballot64(valid);
     if (vmask == 0) return;
-    uint32_t id = valid ? *id_ptr : 0u;
     int nx = (int)ext.x + 1, ny = (int)ext.y + 1;
     int i_lo = (int)lo.x + 64, j_lo = (int)lo.y + 64;
     bool small = valid && nx * ny <= kSmallMax;
     uint32_t box = (uint32_t)i_lo | ((uint32_t)j_lo << 8) | ((uint32_t)nx << 16) | ((uint32_t)ny << 24);
-    push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, id, box, lane, vis, W);
+    push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, W, ctri_id);
     u64 big = ballot64(valid && !small);
+    const uint32_t id = (valid && !small) ? ctri_id[ref] : 0u;
     while (big) {
         int src = __builtin_ctzll(big);
         big &= big - 1;
@@ -166,6 +178,62 @@ __device__ __forceinline__ bool box_outside_frustum(const float (&M)[16], float 
         outside = outside || (dmax < -eps * mag);
     }
     return outside;
+}
+
+constexpr uint32_t kNoPixel = 0xFFFFFFFFu;   // box_footprint: the box cannot cover any pixel centre
+
+// Screen footprint and nearest possible depth of a box, for the occlusion test made when the
+// cluster is popped.  Every triangle inside the box rasterises with a depth that is a convex
+// combination of clip w values attained inside the box, onto pixels inside the projection of the
+// box.  So if the smallest w over the box (minus a rounding margin) is larger than the depth
+// already stored at every pixel whose centre the projected box can reach, nothing in the box can
+// win the z-test.  Returns the packed test record, or 0 when no bound can be given (the box
+// may reach the eye plane, or is more than 8 pixels wide or high):
+//   bit 0 testable | x0 7 bits | y0 7 bits | width-1 3 bits | height-1 3 bits | top 19 bits of the
+//   w bound (truncated, i.e. rounded towards the eye)
+__device__ __forceinline__ uint32_t box_footprint(const float (&M)[16], const FrameParams& fp, float lx, float ly,
+                                                 float lz, float hx, float hy, float hz, uint32_t& wbits19) {
+    const float eps = 1.52587890625e-05f;   // 2^-16
+    wbits19 = 0u;
+    float ax = fmaxf(fabsf(lx), fabsf(hx)), ay = fmaxf(fabsf(ly), fabsf(hy)), az = fmaxf(fabsf(lz), fabsf(hz));
+    float wmin = M[15] + fminf(M[12] * lx, M[12] * hx) + fminf(M[13] * ly, M[13] * hy) + fminf(M[14] * lz, M[14] * hz);
+    float wmag = fmaf(fabsf(M[12]), ax, fmaf(fabsf(M[13]), ay, fmaf(fabsf(M[14]), az, fabsf(M[15]))));
+    float wcons = wmin - eps * wmag;
+    if (!(wcons > 0.0f)) return 0u;
+    float x0 = 3.0e38f, x1 = -3.0e38f, y0 = 3.0e38f, y1 = -3.0e38f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float x = (k & 1) ? hx : lx, y = (k & 2) ? hy : ly, z = (k & 4) ? hz : lz;
+        float cx = fmaf(M[2], z, fmaf(M[1], y, fmaf(M[0], x, M[3])));
+        float cy = fmaf(M[6], z, fmaf(M[5], y, fmaf(M[4], x, M[7])));
+        float cw = fmaf(M[14], z, fmaf(M[13], y, fmaf(M[12], x, M[15])));
+        float rw = __builtin_amdgcn_rcpf(fmaxf(cw, wcons));   // approximate is fine: a whole pixel of slack follows
+        float sx = cx * rw, sy = cy * rw;
+        x0 = fminf(x0, sx); x1 = fmaxf(x1, sx);
+        y0 = fminf(y0, sy); y1 = fmaxf(y1, sy);
+    }
+    // pixels whose centres (i + 0.5) lie inside the projected box, with 1/64 pixel of slack for
+    // vertex snapping (1/512 px) and rounding; none at all means nothing in the box can cover a centre
+    const float hw = 0.5f * (float)fp.W, hh = 0.5f * (float)fp.H, slack = 0.015625f;
+    float fx0 = ceilf(fmaf(x0, hw, hw) - 0.5f - slack), fx1 = floorf(fmaf(x1, hw, hw) - 0.5f + slack);
+    float fy0 = ceilf(fmaf(y0, hh, hh) - 0.5f - slack), fy1 = floorf(fmaf(y1, hh, hh) - 0.5f + slack);
+    if (!(fx0 == fx0 && fx1 == fx1 && fy0 == fy0 && fy1 == fy1)) return 0u;   // NaN somewhere: no bound
+    fx0 = fmaxf(fx0, 0.0f); fy0 = fmaxf(fy0, 0.0f);
+    fx1 = fminf(fx1, (float)(fp.W - 1)); fy1 = fminf(fy1, (float)(fp.H - 1));
+    if (fx0 > fx1 || fy0 > fy1) return kNoPixel;
+    int ix0 = (int)fx0, ix1 = (int)fx1, iy0 = (int)fy0, iy1 = (int)fy1;
+    int bw = ix1 - ix0, bh = iy1 - iy0;
+    if (bw > 7 || bh > 7) return 0u;
+    wbits19 = __float_as_uint(wcons) >> 12;
+    return 1u | ((uint32_t)ix0 << 1) | ((uint32_t)iy0 << 8) | ((uint32_t)bw << 15) | ((uint32_t)bh << 18);
+}
+
+// Depth bin of a survivor record: exponent and top three mantissa bits of its w bound, i.e.
+// eight bins per octave from 2^-7 upwards; records without a bound (near or large boxes) go first.
+__device__ __forceinline__ int depth_bin(u64 e) {
+    if (!((e >> 24) & 1ull)) return 0;
+    int k = (int)(e >> 53) - 120 * 8;     // wbits19 >> 8
+    return min(max(k, 0), kDepthBins - 1);
 }
 
 // One lane per queued straddling triangle: clip, project, fan, hand the pieces to emit().
@@ -220,15 +288,21 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     uint32_t pxy[kMaxPoly];
     float piw[kMaxPoly];
     bool ok = true;
-    for (int i = 0; i < cnt; ++i) ok = project(px[cur][i], fp, pxy[i], piw[i]) && ok;
+    for (int i = 0; i < cnt; ++i) {
+        bool unused;
+        ok = project(px[cur][i], fp, pxy[i], piw[i], unused) && ok;
+    }
     if (!ok) cnt = 0;
-    const BPS_GLOBAL uint32_t* id_ptr = gptr(sc.ctri_id) + (size_t)c * 128 + slot;
+    const BPS_GLOBAL uint32_t* ctri_id = gptr(sc.ctri_id);
+    const uint32_t tri_ref = c * 128u + slot;
     for (int i = 1; ; ++i) {
         bool v = i + 1 < cnt;
         if (ballot64(v) == 0) break;
         uint32_t a = v ? pxy[0] : 0u, b = v ? pxy[i] : 0u, d = v ? pxy[i + 1] : 0u;
         float wa = v ? piw[0] : 0.0f, wb = v ? piw[i] : 0.0f, wd = v ? piw[i + 1] : 0.0f;
-        emit(L, small_count, v, a, b, d, wa, wb, wd, id_ptr, lane, vis, fp.H, fp.W);
+        short2v lo, ext;
+        const bool has = centre_box(a, b, d, fp.H, fp.W, lo, ext);
+        emit(L, small_count, v && has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, fp.W);
     }
 }
 
@@ -264,11 +338,18 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     L.smallq = reinterpret_cast<uint32_t*>(wbase + 64 * 12);
     L.clipq = reinterpret_cast<uint32_t*>(wbase + 64 * 12 + 8 * 64 * 4);
 
-    uint16_t* list = reinterpret_cast<uint16_t*>(smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes);
-    uint32_t* counters = reinterpret_cast<uint32_t*>(smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes +
-                                                     (size_t)fp.round_blocks * 128);
+    unsigned char* shared = smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes;
+    u64* list = reinterpret_cast<u64*>(shared);                                 // [list_cap] surviving clusters
+    uint16_t* order = reinterpret_cast<uint16_t*>(shared + (size_t)fp.list_cap * 8);   // [kOrderCap] blocks, near to far
+    uint16_t* perm = reinterpret_cast<uint16_t*>(shared + (size_t)fp.list_cap * 8 + kOrderCap * 2);   // [list_cap] pop order
+    uint16_t* slot_in_bin = perm + fp.list_cap;                                                       // [list_cap]
+    uint32_t* hist = reinterpret_cast<uint32_t*>(slot_in_bin + fp.list_cap);                          // [2][kDepthBins]
+    uint32_t* counters = hist + 2 * kDepthBins;
     uint32_t* list_count = counters;       // survivors appended in this round
     uint32_t* pop_count = counters + 1;    // survivors handed out in this round
+    uint32_t* next_block = counters + 2;   // blocks handed out so far (whole item)
+    uint32_t* reserved = counters + 3;     // upper bound on list_count once every tester has appended
+    uint32_t* blocks_in_view = counters + 4;   // blocks of the item that are not wholly outside the frustum
 
     const WorkItem item = items[blockIdx.x];
     const SceneDev sc = scenes[item.scene];
@@ -280,8 +361,14 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
 
     int small_count = 0, clip_count = 0;
     // diagnostics (only when the host passes a counter block): per-wave tallies, one atomic each at the end
-    uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0;
+    uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0, st_hidden = 0;
     const unsigned long long t_start = stats ? wall_clock64() : 0ull;
+    // phase timers (diagnostics only): ticks[k] accumulates the time since the previous TICK
+    unsigned long long t_prev = t_start, t_c0 = 0;
+    uint32_t ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define TICK(k) do { if (fp.phase_timers) { unsigned long long t_ = wall_clock64(); ticks[k] += (uint32_t)(t_ - t_prev); t_prev = t_; } } while (0)
+#define TICKC0() do { if (stats) t_c0 = wall_clock64(); } while (0)
+#define TICKC(k) do { if (stats) ticks[k] += (uint32_t)(wall_clock64() - t_c0); } while (0)
     const uint32_t full_tri_mask = 0x00FFFFFFu;
     const BPS_GLOBAL float* g_cverts = gptr(sc.cverts);
     const BPS_GLOBAL uint32_t* g_ctris = gptr(sc.ctris);
@@ -290,20 +377,82 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     const uint32_t S = item.n_splits;
     const uint32_t nblocks_total = (sc.n_clusters + 63u) / 64u;
     const uint32_t nb_item = nblocks_total > item.split ? (nblocks_total - item.split + S - 1u) / S : 0u;
-    const uint32_t RB = (uint32_t)fp.round_blocks;
+    const BPS_GLOBAL float* g_bbounds = gptr(sc.bbounds);
+    const bool occlusion = fp.cull > 1;
+    const uint32_t* vis_hi = reinterpret_cast<const uint32_t*>(vis) + 1;   // depth word of pixel p is vis_hi[2 p]
 
-    // The item's clusters are the 64-cluster blocks split, split + S, ... of its scene.  They are
-    // handled in rounds of RB blocks:
-    //   phase A  every lane tests one cluster's bounds against the frustum; survivors are appended
-    //            (ballot + prefix count, one LDS atomic per wavefront) to the work-group's list
-    //   phase B  wavefronts pop clusters from the list one at a time until it is empty
-    for (uint32_t rb = 0; rb < nb_item; rb += RB) {
-        if (tid == 0) { *list_count = 0u; *pop_count = 0u; }
+    // ---- prologue: counters, and the item's blocks ordered near to far
+    if (tid < 8) counters[tid] = 0u;
+    __syncthreads();
+    const bool sorted = fp.cull != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)fp.list_cap && nb_item > 1;
+    if (sorted) {
+        // key: smallest clip w over the block's bounding box (exactly attained at a corner), as a
+        // sortable integer so that any bit pattern, NaN included, has a unique rank
+        uint32_t* keys = reinterpret_cast<uint32_t*>(list);
+        for (uint32_t b = tid; b < nb_item; b += NT) {
+            const uint32_t gb = b * S + item.split;
+            float wmin = M[15];
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                float lo = g_bbounds[(size_t)a * sc.b_stride + gb], hi = g_bbounds[(size_t)(a + 3) * sc.b_stride + gb];
+                wmin += fminf(M[12 + a] * lo, M[12 + a] * hi);
+            }
+            uint32_t u = __float_as_uint(wmin);
+            uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+            // blocks wholly outside one frustum plane sort last and are never visited
+            float lo[3], hi[3];
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                lo[a] = g_bbounds[(size_t)a * sc.b_stride + gb];
+                hi[a] = g_bbounds[(size_t)(a + 3) * sc.b_stride + gb];
+            }
+            if (box_outside_frustum(M, lo[0], lo[1], lo[2], hi[0], hi[1], hi[2])) key = 0xFFFFFFFFu;
+            else atomicAdd(blocks_in_view, 1u);
+            keys[b] = key;
+        }
         __syncthreads();
-        const uint32_t rb_end = min(rb + RB, nb_item);
-        for (uint32_t jb = rb + (uint32_t)wave; jb < rb_end; jb += NW) {
+        for (uint32_t b = tid; b < nb_item; b += NT) {
+            const uint32_t kb = keys[b];
+            uint32_t rank = 0;
+            for (uint32_t o = 0; o < nb_item; ++o) {
+                const uint32_t ko = keys[o];
+                rank += (ko < kb || (ko == kb && o < b)) ? 1u : 0u;
+            }
+            order[rank] = (uint16_t)b;
+        }
+    }
+    __syncthreads();
+    const uint32_t nb_visit = sorted ? *blocks_in_view : nb_item;
+
+    // The item's clusters are the 64-cluster blocks split, split + S, ... of its scene, visited
+    // near to far in rounds:
+    //   phase A  wavefronts take blocks from the ordered list; every lane tests one cluster's
+    //            bounds against the frustum and works out its screen footprint; survivors are
+    //            appended (ballot + prefix count, one LDS atomic per wavefront) to the work-group's
+    //            list until enough are queued or the list could overflow
+    //   phase B  wavefronts pop clusters from the list one at a time; a cluster whose footprint
+    //            pixels all hold nearer depths by then is skipped (one lane per footprint pixel)
+    TICK(0);
+    for (;;) {
+        for (;;) {
+            if (*list_count >= (uint32_t)fp.round_target) break;
+            uint32_t r0 = 0, blk = 0;
+            if (lane == 0) r0 = atomicAdd(reserved, 64u);
+            r0 = __builtin_amdgcn_readfirstlane(r0);
+            if (r0 + 64u > (uint32_t)fp.list_cap) {
+                if (lane == 0) atomicSub(reserved, 64u);
+                break;
+            }
+            if (lane == 0) blk = atomicAdd(next_block, 1u);
+            blk = __builtin_amdgcn_readfirstlane(blk);
+            if (blk >= nb_visit) {
+                if (lane == 0) atomicSub(reserved, 64u);
+                break;
+            }
+            const uint32_t jb = sorted ? (uint32_t)order[blk] : blk;
             const uint32_t cl = (jb * S + item.split) * 64u + (uint32_t)lane;
             bool visible = cl < sc.n_clusters;
+            uint32_t foot = 0u, wb19 = 0u;
             st_tested += (uint32_t)__popcll(ballot64(visible));
             if (fp.cull) {
                 const uint32_t cc = visible ? cl : 0u;
@@ -311,47 +460,87 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 float hx = g_bounds[3 * sc.c_stride + cc], hy = g_bounds[4 * sc.c_stride + cc],
                       hz = g_bounds[5 * sc.c_stride + cc];
                 visible = visible && !box_outside_frustum(M, lx, ly, lz, hx, hy, hz);
+                if (occlusion && visible) {
+                    foot = box_footprint(M, fp, lx, ly, lz, hx, hy, hz, wb19);
+                    visible = foot != kNoPixel;
+                }
             }
             const u64 keep = ballot64(visible);
-            if (keep) {
-                uint32_t base = 0;
-                if (lane == 0) base = atomicAdd(list_count, (uint32_t)__popcll(keep));
-                base = __builtin_amdgcn_readfirstlane(base);
-                if (visible) list[base + rank_below(keep)] = (uint16_t)(((jb - rb) << 6) | (uint32_t)lane);
+            const uint32_t n_keep = (uint32_t)__popcll(keep);
+            uint32_t base = 0;
+            if (lane == 0) {
+                base = atomicAdd(list_count, n_keep);
+                atomicSub(reserved, 64u - n_keep);
             }
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (visible) list[base + rank_below(keep)] = (u64)cl | ((u64)foot << 24) | ((u64)wb19 << 45);
         }
+        TICK(1);
         __syncthreads();
+        TICK(2);
         const uint32_t n_list = *list_count;
+        if (n_list == 0 && *next_block >= nb_visit) break;
         st_boxed += wave == 0 ? n_list : 0u;
 
-        // pop one ahead so that the next cluster's words are in flight while this one is processed
+        // Order the round's survivors near to far (counting sort on a logarithmic depth key, eight
+        // bins per octave) so that occluders are drawn before what they hide.
+        const bool by_depth = occlusion && n_list > 64u;
+        if (by_depth) {
+            for (int b = tid; b < 2 * kDepthBins; b += NT) hist[b] = 0u;
+            __syncthreads();
+            for (uint32_t i = tid; i < n_list; i += NT)
+                slot_in_bin[i] = (uint16_t)atomicAdd(&hist[depth_bin(list[i])], 1u);
+            __syncthreads();
+            if (tid < kDepthBins) {
+                uint32_t before = 0;
+                for (int b = 0; b < tid; ++b) before += hist[b];
+                hist[kDepthBins + tid] = before;
+            }
+            __syncthreads();
+            for (uint32_t i = tid; i < n_list; i += NT)
+                perm[hist[kDepthBins + depth_bin(list[i])] + slot_in_bin[i]] = (uint16_t)i;
+            __syncthreads();
+            TICK(3);
+        }
+
+        // pop one ahead so that the next cluster's words are in flight while this one is processed;
+        // a cluster whose footprint pixels all hold nearer depths by now cannot win anywhere and is
+        // dropped here (one lane per footprint pixel)
         uint32_t pop = 0;
-        if (lane == 0) pop = atomicAdd(pop_count, 1u);
-        pop = __builtin_amdgcn_readfirstlane(pop);
         float nx_ = 0, ny_ = 0, nz_ = 0;
         uint32_t nt0 = 0, nt1 = 0, c_next = 0;
-        if (pop < n_list) {
-            const uint32_t e = list[pop];
-            c_next = ((rb + (e >> 6)) * S + item.split) * 64u + (e & 63u);
-            const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
-            nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
-            const BPS_GLOBAL uint32_t* ct = g_ctris + (size_t)c_next * 128;
-            nt0 = ct[lane]; nt1 = ct[64 + lane];
-        }
-        while (pop < n_list) {
-            const uint32_t c = c_next;
-            float x = nx_, y = ny_, z = nz_;
-            uint32_t t0 = nt0, t1 = nt1;
-            if (lane == 0) pop = atomicAdd(pop_count, 1u);
-            pop = __builtin_amdgcn_readfirstlane(pop);
-            if (pop < n_list) {
-                const uint32_t e = list[pop];
-                c_next = ((rb + (e >> 6)) * S + item.split) * 64u + (e & 63u);
+        auto pop_visible = [&]() {
+            for (;;) {
+                if (lane == 0) pop = atomicAdd(pop_count, 1u);
+                pop = __builtin_amdgcn_readfirstlane(pop);
+                if (pop >= n_list) return;
+                const u64 e = list[by_depth ? (uint32_t)perm[pop] : pop];
+                const uint32_t lo32 = __builtin_amdgcn_readfirstlane((uint32_t)e);
+                const uint32_t hi32 = __builtin_amdgcn_readfirstlane((uint32_t)(e >> 32));
+                c_next = lo32 & 0x00FFFFFFu;
+                const uint32_t foot = (lo32 >> 24) | (hi32 << 8);
+                if (foot & 1u) {
+                    const int fx = (int)((foot >> 1) & 127u), fy = (int)((foot >> 8) & 127u);
+                    const int bw = (int)((foot >> 15) & 7u), bh = (int)((foot >> 18) & 7u);
+                    const uint32_t wbits = (hi32 >> 13) << 12;
+                    const int qx = lane & 7, qy = lane >> 3;
+                    const bool in = qx <= bw && qy <= bh;
+                    const uint32_t d = in ? vis_hi[2 * ((fy + qy) * fp.W + fx + qx)] : 0u;
+                    if (ballot64(in && d >= wbits) == 0) { ++st_hidden; continue; }
+                }
                 const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
                 nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
                 const BPS_GLOBAL uint32_t* ct = g_ctris + (size_t)c_next * 128;
                 nt0 = ct[lane]; nt1 = ct[64 + lane];
+                return;
             }
+        };
+        pop_visible();
+        while (pop < n_list) {
+            const uint32_t c = c_next;
+            float x = nx_, y = ny_, z = nz_;
+            uint32_t t0 = nt0, t1 = nt1;
+            pop_visible();
 
             // ---- vertex phase
             Clip4 cp = to_clip(M, x, y, z);
@@ -367,8 +556,10 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
             if (!all_finite(cp)) oc |= kInvalid;
             uint32_t xy;
             float iw;
-            bool ok = project(cp, fp, xy, iw);
+            bool can_project;
+            bool ok = project(cp, fp, xy, iw, can_project);
             if (oc == 0 && !ok) oc = kInvalid;
+            if (!can_project) oc |= kNoProject;
             const bool all_inside = ballot64(oc != 0) == 0;
             wave_lds_sync();   // earlier reads of the stage are done
             L.stage[lane] = make_float2(__uint_as_float(xy), iw);
@@ -384,16 +575,23 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 const uint32_t i0 = t & 0xFFu, i1 = (t >> 8) & 0xFFu, i2 = t >> 16;
                 float2 a = L.stage[i0], b = L.stage[i1], d = L.stage[i2];
                 bool fast = slot * 64 + lane < ntri;
+                short2v lo, ext;
+                const bool has = centre_box(__float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), fp.H, fp.W,
+                                            lo, ext);
                 if (!all_inside) {
                     uint32_t oa = L.stage_oc[i0], ob = L.stage_oc[i1], od = L.stage_oc[i2];
                     uint32_t o_or = oa | ob | od, o_and = oa & ob & od;
-                    bool live = fast && ((o_or & kInvalid) == 0) && (o_and == 0);
-                    fast = live && o_or == 0;
-                    st_straddle += (uint32_t)__popcll(ballot64(live && o_or != 0));
-                    push_clip(L, clip_count, live && o_or != 0, (c << 7) | (uint32_t)(slot * 64 + lane));
+                    bool live = fast && ((o_or & kInvalid) == 0) && ((o_and & 0x3Fu) == 0);
+                    fast = live && (o_or & 0x3Fu) == 0;
+                    // A straddler whose three vertices all project (w > 0) cannot reach a pixel centre
+                    // outside the box of its projected vertices: only the others need the clipper.
+                    const bool straddle = live && (o_or & 0x3Fu) != 0 && (has || (o_or & kNoProject) != 0);
+                    st_straddle += (uint32_t)__popcll(ballot64(straddle));
+                    push_clip(L, clip_count, straddle, (c << 7) | (uint32_t)(slot * 64 + lane));
                 }
-                emit(L, small_count, fast, __float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), a.y, b.y,
-                     d.y, g_ctri_id + (size_t)c * 128 + slot * 64 + lane, lane, vis, fp.H, fp.W);
+                emit(L, small_count, fast && has, lo, ext, __float_as_uint(a.x), __float_as_uint(b.x),
+                     __float_as_uint(d.x), a.y, b.y, d.y, c * 128u + (uint32_t)(slot * 64 + lane), g_ctri_id, lane, vis,
+                     fp.W);
             }
             // ---- clip queue: full wavefronts only while streaming
             while (clip_count >= 64) {
@@ -402,7 +600,11 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 clip_count -= 64;
             }
         }
+        TICK(5);
         __syncthreads();
+        if (tid == 0) { *list_count = 0u; *pop_count = 0u; *reserved = 0u; }
+        __syncthreads();
+        TICK(6);
     }
     if (clip_count > 0) {
         wave_lds_sync();
@@ -410,19 +612,24 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     }
     if (small_count > 0) {
         wave_lds_sync();
-        drain_small(L, small_count, lane, vis, fp.W);
+        drain_small(L, small_count, lane, vis, fp.W, g_ctri_id);
     }
+    // diagnostics: per-wave tallies go through LDS (the survivor list is free by now) and leave as
+    // one record of 16 words per work-group, without atomics
     if (stats && lane == 0) {
-        atomicAdd(&stats[0], (unsigned long long)st_tested);
-        atomicAdd(&stats[1], (unsigned long long)st_boxed);
-        atomicAdd(&stats[2], (unsigned long long)st_drawn);
-        atomicAdd(&stats[3], (unsigned long long)st_straddle);
-        unsigned long long dt = wall_clock64() - t_start;
-        atomicAdd(&stats[4], dt);
-        atomicMax(&stats[5], dt);
-        if (wave == 0) stats[8 + blockIdx.x] = dt;      // duration of this work-group's first wave
+        uint32_t* rec = reinterpret_cast<uint32_t*>(list) + wave * 16;
+        const uint32_t dt = (uint32_t)(wall_clock64() - t_start);
+        rec[0] = st_tested; rec[1] = st_boxed; rec[2] = st_drawn; rec[3] = st_straddle; rec[4] = st_hidden; rec[5] = dt;
+        for (int k = 0; k < 8; ++k) rec[6 + k] = ticks[k];
     }
     __syncthreads();
+    if (stats && tid < 16) {
+        const uint32_t* rec = reinterpret_cast<const uint32_t*>(list);
+        unsigned long long sum = 0, mx = 0;
+        for (int w = 0; w < NW; ++w) { sum += rec[w * 16 + tid]; mx = max(mx, (unsigned long long)rec[w * 16 + tid]); }
+        stats[(size_t)blockIdx.x * 16 + tid] = tid == 5 ? mx : sum;      // word 5: longest wavefront of the group
+        if (tid == 15) stats[(size_t)blockIdx.x * 16 + 15] = rec[5];     // word 15: first wavefront
+    }
 
     // ---- resolve this work-group's frame
     const size_t base = (size_t)item.env * HW;
@@ -466,6 +673,7 @@ __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n) {
 
 hipError_t prepare_raster(int threads, size_t lds) {
     const void* f = threads == 256   ? reinterpret_cast<const void*>(&k_raster<256>)
+                    : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384>)
                     : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512>)
                                      : reinterpret_cast<const void*>(&k_raster<1024>);
     return hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -476,6 +684,8 @@ void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const
                    uint32_t* out_id, unsigned long long* stats) {
     if (threads == 256)
         hipLaunchKernelGGL(k_raster<256>, grid, dim3(256), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
+    else if (threads == 384)
+        hipLaunchKernelGGL(k_raster<384>, grid, dim3(384), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
     else if (threads == 512)
         hipLaunchKernelGGL(k_raster<512>, grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
     else

@@ -119,7 +119,8 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
             SVert sv[kMaxPoly];
             bool ok = true;
             for (int q = 0; q < cnt; ++q) {
-                ok = project(poly[cur][q].c, fp, sv[q].xy, sv[q].iw) && ok;
+                bool unused;
+                ok = project(poly[cur][q].c, fp, sv[q].xy, sv[q].iw, unused) && ok;
                 sv[q].r = poly[cur][q].r;
                 sv[q].g = poly[cur][q].g;
                 sv[q].b = poly[cur][q].b;

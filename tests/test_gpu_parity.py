@@ -72,8 +72,12 @@ def test_cluster_culling_never_changes_a_frame():
     ref = _oracle(w)
     a = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W)
     b = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, flags=bps.FLAG_NO_CLUSTER_CULL)
-    _compare(a[0], a[1], ref, "culling on")
+    c = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, flags=bps.FLAG_NO_OCCLUSION_CULL)
+    d = _render_gpu(w.scenes, w.scene_ids, w.view_proj, w.H, w.W, splits=3)
+    _compare(a[0], a[1], ref, "frustum + occlusion culling")
     _compare(b[0], b[1], ref, "culling off")
+    _compare(c[0], c[1], ref, "frustum culling only")
+    _compare(d[0], d[1], ref, "culling with split frames")
     # cameras with pitch and roll-free tilt, close to walls: bounds straddle every plane
     Ms = np.stack([synth.view_proj_from_pose((1.0 + 1.1 * k, 0.3 + 0.1 * k, 0.7 * k + 0.4), 0.8 * k, 0.3 * (k % 5 - 2))
                    for k in range(16)])
