@@ -1,11 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the batch renderer hot path on one MI355X.
 
-A step is one complete render request (request staging + the fused raster kernel, plus the
-resolve kernel when frames are split) for the headline workload: 4 procedural multi-room
-scenes of ~500k triangles, 1024 environments (256 per scene, interleaved), 64x64 float32
-depth.  Scenes and view-projection matrices are resident in HBM before the timed region.
+A step is one complete render request (request staging, dispatch planning, the fused raster
+kernel, plus the resolve kernel when frames are split) for the headline workload: 4 procedural
+multi-room scenes of ~500k triangles, 1024 environments (256 per scene, interleaved), 64x64
+float32 depth.  Scenes and view-projection matrices are resident in HBM before the timed region.
 Prints ONE JSON line.
+
+Two roofline objects are reported, both against the published HBM peak:
+  roofline              the timed configuration (cluster culling on).  Algorithmic bytes are
+                        recomputed for culling: bounds of every block / cluster that was tested plus
+                        the mesh bytes of the clusters that reached the triangle phase, plus output.
+  roofline_full_stream  the same request with culling off (every environment streams its whole
+                        scene): 12 B per triangle + 12 B per vertex per environment, plus output.
 """
 import argparse
 import json
@@ -21,12 +28,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
-def algorithmic_bytes(w):
-    """Bytes the method itself must move per request: every environment streams its scene's
-    index and vertex arrays once (12 B per triangle + 12 B per vertex), the frames are written
-    once (4 B per pixel), and the request (scene id + matrix, 68 B) is read once."""
+def full_stream_bytes(w):
+    """Every environment streams its scene's index and vertex arrays once (12 B per triangle +
+    12 B per vertex), the frames are written once (4 B per pixel, +3 B with colour), and the
+    request (scene id + matrix, 68 B) is read once."""
     geo = sum(12 * w.scenes[s].T + 12 * w.scenes[s].V for s in w.scene_ids)
-    out = w.B * w.H * w.W * 4
+    out = w.B * w.H * w.W * (7 if w.rgbd else 4)
     return geo + out + w.B * 68
 
 
@@ -36,23 +43,69 @@ def cpu_baseline(w, n_envs):
     stride = max(1, w.B // n_envs)
     sel = np.arange(0, w.B, stride)[:n_envs]
     t0 = time.perf_counter()
-    r = oracle.render_batch(w.scenes, w.scene_ids[sel], w.view_proj[sel], w.H, w.W)
+    r = oracle.render_batch(w.scenes, w.scene_ids[sel], w.view_proj[sel], w.H, w.W, rgbd=w.rgbd)
     dt = time.perf_counter() - t0
     return dict(value=len(sel) / dt, unit="frames/s", cores=int(r["threads"]), kind="oracle",
                 sample=f"{len(sel)} of {w.B} environments (every {stride}th), same scenes and matrices, {dt:.2f} s wall")
 
 
+def measured_traffic(key):
+    """HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/ (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get(key)
+    except (OSError, ValueError):
+        return None
+
+
+def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False):
+    mode = bps.MODE_RGBD if w.rgbd else bps.MODE_DEPTH
+    r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, mode=mode, splits=splits, threads=threads, flags=flags)
+    handles = [r.load_scene(s.vertices, s.indices, s.colors if w.rgbd else None) for s in w.scenes]
+    ids = np.array([handles[k] for k in w.scene_ids], np.int32)
+    vp = torch.from_numpy(w.view_proj).cuda()
+    depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
+    rgb = torch.empty((w.B, w.H, w.W, 3), dtype=torch.uint8, device="cuda") if w.rgbd else None
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
+    torch.cuda.synchronize()
+    bps.bps_set_profiling(r.handle, True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    launches, kernel_ms = bps.bps_kernel_ms_total(r.handle)
+    bps.bps_set_profiling(r.handle, False)
+    res = dict(dt=dt, kernel_ms_avg=kernel_ms / max(launches, 1), launches=launches,
+               clusters=[bps.bps_query(r.handle, h, 0) for h in handles],
+               splits=bps.bps_query(r.handle, handles[0], 4), groups=bps.bps_query(r.handle, handles[0], 5),
+               threads=bps.bps_query(r.handle, handles[0], 6), lds=bps.bps_query(r.handle, handles[0], 7))
+    if diagnostics:
+        bps.bps_set_diagnostics(r.handle, 1)
+        bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
+        res["diag"] = bps.bps_read_diagnostics(r.handle, 1 << 20).reshape(-1, 16).astype(np.float64)
+        bps.bps_set_diagnostics(r.handle, 0)
+    r.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="workload number (3 = headline)")
     ap.add_argument("--batch", type=int, default=None, help="override the environment count")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
-    ap.add_argument("--no-cull", action="store_true", help="stream every cluster (no frustum culling of clusters)")
+    ap.add_argument("--no-cull", action="store_true", help="stream every cluster (no culling of clusters)")
     ap.add_argument("--no-occlusion", action="store_true", help="frustum culling of clusters only")
+    ap.add_argument("--no-dispatch-order", action="store_true", help="launch work-groups in batch order")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed run: no diagnostics request, no full-stream run (for profiler runs)")
     ap.add_argument("--cpu-envs", type=int, default=512, help="environments in the oracle timing sample (0 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of rendering, run a plain device-to-device copy of this many MiB five times "
@@ -82,34 +135,44 @@ def main():
         sys.exit("bench.py: no GPU visible; the renderer has no CPU path")
 
     w = synth.build_config(args.config, B=args.batch)
-    if w.rgbd:
-        sys.exit("bench.py: RGB-D workloads are not wired into the benchmark yet")
-    r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, splits=args.splits, threads=args.threads,
-                     flags=(bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0) |
-                           (bps.FLAG_NO_OCCLUSION_CULL if args.no_occlusion else 0))
-    handles = [r.load_scene(s.vertices, s.indices, None) for s in w.scenes]
-    ids = np.array([handles[k] for k in w.scene_ids], np.int32)
-    vp = torch.from_numpy(w.view_proj).cuda()
-    depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
-    stream = torch.cuda.current_stream()
+    flags = ((bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0) | (bps.FLAG_NO_OCCLUSION_CULL if args.no_occlusion else 0) |
+             (bps.FLAG_NO_DISPATCH_ORDER if args.no_dispatch_order else 0))
+    culling = not args.no_cull
+    main_run = timed_run(bps, torch, w, flags, args.steps, args.warmup, args.splits, args.threads,
+                         diagnostics=culling and not args.no_extras)
+    dt = main_run["dt"]
+    kernel_ms_avg = main_run["kernel_ms_avg"]
+    variant = "full_stream" if args.no_cull else ("frustum_cull" if args.no_occlusion else "cull")
 
-    for _ in range(args.warmup):
-        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
-    torch.cuda.synchronize()
-    bps.bps_set_profiling(r.handle, True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    launches, kernel_ms = bps.bps_kernel_ms_total(r.handle)
-    bps.bps_set_profiling(r.handle, False)
+    fbytes = full_stream_bytes(w)
+    if culling and "diag" in main_run:
+        per_scene = [((12.0 * s.T + 12.0 * s.V) / c, c) for s, c in zip(w.scenes, main_run["clusters"])]
+        diag = main_run["diag"]
+        # the scenes of one workload have near-identical cluster sizes: use the average bytes per cluster
+        avg_cluster_bytes = float(np.mean([p[0] for p in per_scene]))
+        blocks = sum((per_scene[s][1] + 63) // 64 for s in w.scene_ids)
+        abytes = (float(diag[:, 2].sum()) * avg_cluster_bytes + 24.0 * (blocks + float(diag[:, 0].sum())) +
+                  w.B * w.H * w.W * (7 if w.rgbd else 4) + w.B * 68)
+        accounting = ("culling: 24 B bounds per block and per tested cluster + mesh bytes (12 B/triangle + 12 B/vertex, "
+                      "scene average per cluster) of clusters that reached the triangle phase + output + request")
+        extra = {"clusters_tested": int(diag[:, 0].sum()), "clusters_kept_by_bounds_tests": int(diag[:, 1].sum()),
+                 "clusters_drawn": int(diag[:, 2].sum()), "clusters_skipped_as_occluded": int(diag[:, 4].sum()),
+                 "clusters_in_batch": int(sum(per_scene[s][1] for s in w.scene_ids))}
+    elif culling:
+        abytes, accounting, extra = None, "culling on; diagnostics skipped (--no-extras)", {}
+    else:
+        abytes = fbytes
+        accounting = "full stream: 12 B/triangle + 12 B/vertex per environment + output + request"
+        extra = {}
 
-    ms_per_step = dt * 1e3 / args.steps
-    kernel_ms_avg = kernel_ms / max(launches, 1)
-    abytes = algorithmic_bytes(w)
-    achieved = abytes / (kernel_ms_avg * 1e-3) / 1e9
-    clusters = sum(bps.bps_query(r.handle, h, 0) for h in handles)
+    def roofline(nbytes, ms, note, traffic_key):
+        if nbytes is None:
+            return None
+        achieved = nbytes / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(traffic_key), "kernel": "k_raster",
+                "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes, "accounting": note}
+
     out = {
         "metric": "rendered frames/sec (64x64 depth, 1024 envs) on 1 MI355X",
         "value": w.B * args.steps / dt,
@@ -117,41 +180,40 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": dt * 1e3 / args.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"config{w.number}: {len(w.scenes)} procedural multi-room scenes x ~{w.scenes[0].T} triangles, "
-                        f"{w.B} environments (scene = b mod {len(w.scenes)}), {w.H}x{w.W} float32 depth",
+            "workload": f"config{w.number}: {len(w.scenes)} procedural {'multi-room' if w.number > 1 else 'room'} scenes x "
+                        f"~{w.scenes[0].T} triangles, {w.B} environments (scene = b mod {len(w.scenes)}), "
+                        f"{w.H}x{w.W} {'RGB-D' if w.rgbd else 'float32 depth'}",
+            "variant": variant,
             "B": w.B, "H": w.H, "W": w.W, "scenes": len(w.scenes),
             "triangles_per_scene": [s.T for s in w.scenes],
             "env_triangles_per_step": w.env_triangles,
-            "clusters_total": clusters,
-            "splits": bps.bps_query(r.handle, handles[0], 4),
-            "work_groups": bps.bps_query(r.handle, handles[0], 5),
-            "threads": bps.bps_query(r.handle, handles[0], 6),
-            "lds_bytes": bps.bps_query(r.handle, handles[0], 7),
+            "splits": main_run["splits"], "work_groups": main_run["groups"], "threads": main_run["threads"],
+            "lds_bytes": main_run["lds"],
         },
         "env_triangles_per_s": w.env_triangles * args.steps / dt,
-        "roofline": {
-            "bound": "hbm",
-            "achieved": achieved,
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
-            "kernel": "k_raster",
-            "kernel_ms_avg": kernel_ms_avg,
-            "launches_timed": launches,
-            "algorithmic_bytes_per_launch": abytes,
-        },
+        "roofline": roofline(abytes, kernel_ms_avg, accounting, f"config{w.number}_{variant}"),
     }
+    if out["roofline"] is not None:
+        out["roofline"].update(extra)
+        out["roofline"]["launches_timed"] = main_run["launches"]
+    if culling and not args.no_extras:
+        steps2 = max(5, args.steps // 5)
+        fs = timed_run(bps, torch, w, bps.FLAG_NO_CLUSTER_CULL, steps2, 3, args.splits, args.threads)
+        rl = roofline(fbytes, fs["kernel_ms_avg"],
+                      "full stream: 12 B/triangle + 12 B/vertex per environment + output + request; same request "
+                      "with cluster culling switched off", f"config{w.number}_full_stream")
+        rl["frames_per_s"] = w.B * steps2 / fs["dt"]
+        rl["launches_timed"] = fs["launches"]
+        out["roofline_full_stream"] = rl
     if args.cpu_envs > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_envs)
-    r.close()
     print(json.dumps(out))
 
 

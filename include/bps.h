@@ -47,7 +47,8 @@ enum { BPS_MODE_DEPTH = 0, BPS_MODE_RGBD = 1 };
  * (Sec. 3.2 "Pipelined geometry culling"); it never changes a frame, only the work done. */
 enum {
     BPS_FLAG_NO_CLUSTER_CULL = 1,   /* stream every cluster of the scene for every environment */
-    BPS_FLAG_NO_OCCLUSION_CULL = 2  /* frustum culling only: do not skip clusters hidden behind nearer geometry */
+    BPS_FLAG_NO_OCCLUSION_CULL = 2, /* frustum culling only: do not skip clusters hidden behind nearer geometry */
+    BPS_FLAG_NO_DISPATCH_ORDER = 4  /* launch work-groups in batch order instead of costliest first */
 };
 
 typedef struct {

@@ -100,6 +100,8 @@ void free_scene(HostScene& s) {
     s = HostScene{};
 }
 
+bool fp_cull_enabled(const bps_renderer* r) { return !(r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL); }
+
 // Choose how many work-groups share one environment: enough groups to fill the device a few
 // times over when the batch is small, one group per environment when the batch is large.
 int plan_splits(const bps_renderer* r, uint32_t B, uint32_t min_clusters) {
@@ -129,7 +131,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
     if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 384 && cfg->threads != 512 && cfg->threads != 1024)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 384, 512 or 1024");
     if (cfg->splits < 0) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be >= 0");
-    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
+    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL | BPS_FLAG_NO_DISPATCH_ORDER)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
         return fail(nullptr, BPS_ERR_HIP, "bps_create: no HIP device available (this library has no CPU path)");
@@ -399,7 +401,11 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     const size_t items_bytes = n_items * sizeof(bps::WorkItem);
     const size_t vp_bytes = (size_t)B * 16 * sizeof(float);
     const size_t ids_bytes = rgbd ? (size_t)B * sizeof(uint32_t) : 0;
-    const size_t need = items_bytes + ids_bytes + vp_bytes;
+    // costliest-first dispatch pays off once the launch no longer fits on the device in one go
+    const bool planned = fp_cull_enabled(r) && n_items > (size_t)2 * r->num_cu && n_items <= bps::kMaxPlannedItems &&
+                         !(r->cfg.flags & BPS_FLAG_NO_DISPATCH_ORDER);
+    const size_t plan_bytes = planned ? 2 * n_items * sizeof(uint32_t) : 0;
+    const size_t need = items_bytes + ids_bytes + vp_bytes + plan_bytes;
     RingSlot& slot = r->ring[r->ring_next];
     r->ring_next = (r->ring_next + 1) % kRing;
     if (slot.pending) {
@@ -427,6 +433,8 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(slot.dev);
     const uint32_t* d_env_scene = reinterpret_cast<const uint32_t*>(slot.dev + items_bytes);
     const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(slot.dev + items_bytes + ids_bytes);
+    uint32_t* d_cost = reinterpret_cast<uint32_t*>(slot.dev + items_bytes + ids_bytes + vp_bytes);
+    uint32_t* d_dispatch = planned ? d_cost + n_items : nullptr;
 
     // ---- RGB-D: the colour pass needs the winning triangle ids even when the caller does not
     if (rgbd && !out_tri_id) {
@@ -480,8 +488,12 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         ev_stop = r->ev[r->ev_used + 1];
         r->ev_used += 2;
     }
+    if (planned) {
+        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, (uint32_t)n_items, d_cost, d_dispatch);
+        BPS_HIP(r, hipGetLastError());
+    }
     bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, d_items, d_vp, fp, r->gvis, out_depth,
-                       out_tri_id, d_stats);
+                       out_tri_id, d_stats, d_dispatch);
     BPS_HIP(r, hipGetLastError());
     if (S > 1) {
         size_t n = (size_t)B * HW;

@@ -76,7 +76,7 @@ template <int NT>
 __global__ void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                          const float* __restrict__ view_proj, FrameParams fp, unsigned long long* __restrict__ gvis,
                          float* __restrict__ out_depth, uint32_t* __restrict__ out_id,
-                         unsigned long long* __restrict__ stats);
+                         unsigned long long* __restrict__ stats, const uint32_t* __restrict__ dispatch);
 
 __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float background,
                           float* __restrict__ out_depth, uint32_t* __restrict__ out_id);
@@ -86,7 +86,11 @@ __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n);
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
-                   uint32_t* out_id, unsigned long long* stats);
+                   uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch);
+// Fills dispatch[n_items] with the item indices in launch order (costliest first within each die's share).
+constexpr uint32_t kMaxPlannedItems = 16384;   // k_dispatch_order keeps one cost word per item in LDS
+void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
+                 uint32_t n_items, uint32_t* cost, uint32_t* dispatch);
 hipError_t prepare_raster(int threads, size_t lds);
 void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
                   const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb);

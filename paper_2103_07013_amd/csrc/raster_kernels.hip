@@ -322,7 +322,8 @@ template <int NT>
 __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
-                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats) {
+                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats,
+                                               const uint32_t* __restrict__ dispatch) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x;
@@ -351,7 +352,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     uint32_t* reserved = counters + 3;     // upper bound on list_count once every tester has appended
     uint32_t* blocks_in_view = counters + 4;   // blocks of the item that are not wholly outside the frustum
 
-    const WorkItem item = items[blockIdx.x];
+    const WorkItem item = items[dispatch ? dispatch[blockIdx.x] : blockIdx.x];
     const SceneDev sc = scenes[item.scene];
     float M[16];
 #pragma unroll
@@ -661,6 +662,56 @@ __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float
     if (hit) gvis[p] = kEmptyKey;
 }
 
+// Launch planning.  Work-groups are dispatched in index order, so handing out the most expensive
+// items first (longest processing time first) shortens the tail of the launch.  An item's cost
+// is estimated as the number of its scene's 64-cluster blocks that are not wholly outside the
+// environment's frustum; k_dispatch_order then ranks the items of each die's share (index % 8)
+// by decreasing cost.
+__global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
+                                                  const float* __restrict__ view_proj, uint32_t n_items,
+                                                  uint32_t* __restrict__ cost) {
+    const uint32_t i = blockIdx.x;
+    if (i >= n_items) return;
+    const WorkItem item = items[i];
+    const SceneDev sc = scenes[item.scene];
+    float M[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) M[k] = view_proj[(size_t)item.env * 16 + k];
+    const BPS_GLOBAL float* bb = gptr(sc.bbounds);
+    const uint32_t nblocks = (sc.n_clusters + 63u) / 64u;
+    uint32_t count = 0;
+    for (uint32_t gb = item.split + item.n_splits * threadIdx.x; gb < nblocks; gb += item.n_splits * 64u) {
+        float lx = bb[gb], ly = bb[sc.b_stride + gb], lz = bb[2 * sc.b_stride + gb];
+        float hx = bb[3 * sc.b_stride + gb], hy = bb[4 * sc.b_stride + gb], hz = bb[5 * sc.b_stride + gb];
+        count += box_outside_frustum(M, lx, ly, lz, hx, hy, hz) ? 0u : 1u;
+    }
+#pragma unroll
+    for (int sh = 32; sh >= 1; sh >>= 1) count += (uint32_t)__shfl_xor((int)count, sh, 64);
+    if (threadIdx.x == 0) cost[i] = count;
+}
+
+__global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restrict__ cost, uint32_t n_items,
+                                                         uint32_t* __restrict__ dispatch) {
+    extern __shared__ uint32_t s_cost[];
+    for (uint32_t i = threadIdx.x; i < n_items; i += blockDim.x) s_cost[i] = cost[i];
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < n_items; i += blockDim.x) {
+        const uint32_t die = i & 7u, mine = s_cost[i];
+        uint32_t rank = 0;
+        for (uint32_t o = die; o < n_items; o += 8u) {
+            const uint32_t c = s_cost[o];
+            rank += (c > mine || (c == mine && o < i)) ? 1u : 0u;
+        }
+        dispatch[die + 8u * rank] = i;
+    }
+}
+
+void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
+                 uint32_t n_items, uint32_t* cost, uint32_t* dispatch) {
+    hipLaunchKernelGGL(k_item_cost, dim3(n_items), dim3(64), 0, stream, scenes, items, view_proj, n_items, cost);
+    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), n_items * sizeof(uint32_t), stream, cost, n_items, dispatch);
+}
+
 __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0ull;
@@ -681,15 +732,15 @@ hipError_t prepare_raster(int threads, size_t lds) {
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
-                   uint32_t* out_id, unsigned long long* stats) {
+                   uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch) {
     if (threads == 256)
-        hipLaunchKernelGGL(k_raster<256>, grid, dim3(256), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
+        hipLaunchKernelGGL(k_raster<256>, grid, dim3(256), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
     else if (threads == 384)
-        hipLaunchKernelGGL(k_raster<384>, grid, dim3(384), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
+        hipLaunchKernelGGL(k_raster<384>, grid, dim3(384), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
     else if (threads == 512)
-        hipLaunchKernelGGL(k_raster<512>, grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
+        hipLaunchKernelGGL(k_raster<512>, grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
     else
-        hipLaunchKernelGGL(k_raster<1024>, grid, dim3(1024), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats);
+        hipLaunchKernelGGL(k_raster<1024>, grid, dim3(1024), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
 }
 
 }  // namespace bps
