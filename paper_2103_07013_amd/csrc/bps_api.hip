@@ -48,6 +48,7 @@ struct bps_renderer {
     int device = 0;
     int num_cu = 0;
     int threads = 512;
+    int tile_w = 64, tile_h = 64, tiles = 1;
     int list_cap = 2048;
     int round_target = 64;
     size_t lds = 0;
@@ -109,7 +110,8 @@ int plan_splits(const bps_renderer* r, uint32_t B, uint32_t min_clusters) {
     int waves = r->threads / 64;
     int want_groups = 4 * r->num_cu;
     int s = 1;
-    if ((int)B < 2 * r->num_cu) s = (want_groups + (int)B - 1) / (int)B;
+    int groups = (int)B * r->tiles;
+    if (groups < 2 * r->num_cu) s = (want_groups + groups - 1) / groups;
     int max_s = std::max(1, (int)(min_clusters / (uint32_t)(8 * waves)));   // >= 8 clusters per wave
     return std::max(1, std::min(s, max_s));
 }
@@ -157,11 +159,21 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         if (hipDeviceGetAttribute(&lds_optin, hipDeviceAttributeSharedMemPerBlockOptin, r->device) != hipSuccess) lds_optin = 0;
         (void)hipGetLastError();
         r->max_lds = std::max<size_t>(prop.sharedMemPerBlock, (size_t)std::max(lds_optin, 0));
+        // a work-group owns one tile of the frame: the whole frame up to 64 pixels per side,
+        // otherwise the frame is cut into equal tiles of at most 64 pixels
+        auto tile_of = [](int n) { int parts = (n + 63) / 64; return (n + parts - 1) / parts; };
+        r->tile_w = tile_of(cfg->width);
+        r->tile_h = tile_of(cfg->height);
+        if (const char* e = std::getenv("BPS_TILE")) {   // tuning knob: force a tile size
+            int v = std::atoi(e);
+            if (v >= 8 && v <= 128) { r->tile_w = std::min(v, cfg->width); r->tile_h = std::min(v, cfg->height); }
+        }
+        r->tiles = ((cfg->width + r->tile_w - 1) / r->tile_w) * ((cfg->height + r->tile_h - 1) / r->tile_h);
         // preferred work-group size whose LDS footprint leaves room for a useful survivor list
         const int order[4] = {512, 384, 256, 1024};
         r->threads = 0;
         auto fit_cap = [&](int t) -> int {
-            size_t fixed = bps::lds_bytes(cfg->height, cfg->width, t, 0);
+            size_t fixed = bps::lds_bytes(r->tile_h, r->tile_w, t, 0);
             if (fixed >= r->max_lds) return 0;
             // two work-groups per compute unit when the frame allows it
             size_t budget = fixed * 2 + 2 * 12 * 512 <= r->max_lds ? r->max_lds / 2 : r->max_lds;
@@ -176,12 +188,12 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         }
         if (!r->threads)
             return fail(r, BPS_ERR_UNSUPPORTED, "bps_create: a %dx%d frame needs %zu bytes of LDS, device offers %zu",
-                        cfg->height, cfg->width, bps::lds_bytes(cfg->height, cfg->width, cfg->threads ? cfg->threads : 256, 512),
+                        cfg->height, cfg->width, bps::lds_bytes(r->tile_h, r->tile_w, cfg->threads ? cfg->threads : 256, 512),
                         r->max_lds);
         r->list_cap = fit_cap(r->threads);
         r->round_target = r->list_cap / 2;
         if (const char* e = std::getenv("BPS_ROUND_TARGET")) r->round_target = std::max(1, std::atoi(e));   // tuning knob
-        r->lds = bps::lds_bytes(cfg->height, cfg->width, r->threads, r->list_cap);
+        r->lds = bps::lds_bytes(r->tile_h, r->tile_w, r->threads, r->list_cap);
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
         BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
@@ -365,19 +377,20 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         for (uint32_t b = 0; b < B; ++b) order[b] = b;
         std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return scene_ids[a] < scene_ids[b]; });
         std::vector<bps::WorkItem> sorted;
-        sorted.reserve((size_t)B * S);
+        sorted.reserve((size_t)B * S * r->tiles);
         for (uint32_t k = 0; k < B; ++k) {
             uint32_t b = order[k];
             uint32_t C = r->scenes[scene_ids[b]].dev.n_clusters;
             (void)C;
-            for (int s = 0; s < S; ++s) {
-                bps::WorkItem it;
-                it.env = b;
-                it.scene = (uint32_t)scene_ids[b];
-                it.split = (uint32_t)s;
-                it.n_splits = (uint32_t)S;
-                sorted.push_back(it);
-            }
+            for (int tile = 0; tile < r->tiles; ++tile)
+                for (int s = 0; s < S; ++s) {
+                    bps::WorkItem it;
+                    it.env = b;
+                    it.scene = (uint32_t)scene_ids[b];
+                    it.split_of = ((uint32_t)S << 16) | (uint32_t)s;
+                    it.tile = (uint32_t)tile;
+                    sorted.push_back(it);
+                }
         }
         const size_t n = sorted.size();
         r->plan_items.resize(n);
@@ -453,6 +466,8 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     bps::FrameParams fp;
     fp.H = H;
     fp.W = W;
+    fp.tile_w = r->tile_w;
+    fp.tile_h = r->tile_h;
     fp.sx = 128.0f * (float)W;
     fp.sy = 128.0f * (float)H;
     fp.xmax = 2.0f * fp.sx + 64.0f;
@@ -489,7 +504,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         r->ev_used += 2;
     }
     if (planned) {
-        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, (uint32_t)n_items, d_cost, d_dispatch);
+        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch);
         BPS_HIP(r, hipGetLastError());
     }
     bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, d_items, d_vp, fp, r->gvis, out_depth,

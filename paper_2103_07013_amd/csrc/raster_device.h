@@ -84,8 +84,16 @@ __device__ __forceinline__ Setup make_setup(uint32_t xy0, uint32_t xy1, uint32_t
     return s;
 }
 
-// Coverage test and z-test of pixel (i, j) against one set-up triangle.
-__device__ __forceinline__ void shade_pixel(const Setup& s, int i, int j, bool active, uint32_t id, u64* vis, int W) {
+// The part of the frame one work-group owns: pixels [x0, x0 + w) x [y0, y0 + h), and the same
+// rectangle in normalised device coordinates (aL <= x/w <= aR, aT <= y/w <= aB).
+struct Window {
+    int x0, y0, w, h;
+    float aL, aR, aT, aB;
+};
+
+// Coverage test and z-test of pixel (i, j) against one set-up triangle; vis holds the window's pixels.
+__device__ __forceinline__ void shade_pixel(const Setup& s, int i, int j, bool active, uint32_t id, u64* vis,
+                                            const Window& win) {
     int px = (i << 8) + 128 - kOrigin, py = (j << 8) + 128 - kOrigin;
     int E0 = __mul24(s.dx0, py - s.Y1) - __mul24(s.dy0, px - s.X1);
     int E1 = __mul24(s.dx1, py - s.Y2) - __mul24(s.dy1, px - s.X2);
@@ -96,7 +104,7 @@ __device__ __forceinline__ void shade_pixel(const Setup& s, int i, int j, bool a
         float num = fmaf(e2, s.iw2, fmaf(e1, s.iw1, e0 * s.iw0));
         float depth = (float)s.A2 / num;
         u64 key = ((u64)__float_as_uint(depth) << 32) | (u64)id;
-        atomicMin(&vis[j * W + i], key);
+        atomicMin(&vis[(j - win.y0) * win.w + (i - win.x0)], key);
     }
 }
 

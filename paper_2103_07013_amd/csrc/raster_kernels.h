@@ -34,14 +34,15 @@ struct SceneDev {
     uint32_t n_clusters, n_tris, n_verts, c_stride, b_stride, pad;
 };
 
-// One work-group's share: environment `env`, and of its scene the 64-cluster blocks
-// split, split + n_splits, split + 2 n_splits, ...
+// One work-group's share: tile `tile` of environment `env`'s frame, and of its scene the
+// 64-cluster blocks split, split + n_splits, split + 2 n_splits, ... (split_of = n_splits << 16 | split)
 struct WorkItem {
-    uint32_t env, scene, split, n_splits;
+    uint32_t env, scene, split_of, tile;
 };
 
 struct FrameParams {
     int32_t H, W;
+    int32_t tile_w, tile_h; // a work-group owns one tile of the frame (the whole frame when it fits)
     float sx, sy;          // 128*W, 128*H
     float xmax, ymax;      // 2*sx + 64, 2*sy + 64
     float background;
@@ -67,8 +68,8 @@ constexpr int kDepthBins = 128;        // bins of the per-round depth sort of su
 
 // visibility buffer, per-wave blocks, survivor list (8 B record + two 2 B sort words per cluster),
 // block order, depth histogram and its prefix, four counters
-__host__ __device__ inline size_t lds_bytes(int H, int W, int threads, int list_cap) {
-    return (size_t)H * W * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)list_cap * 12 + kOrderCap * 2 +
+__host__ __device__ inline size_t lds_bytes(int tile_h, int tile_w, int threads, int list_cap) {
+    return (size_t)tile_h * tile_w * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)list_cap * 12 + kOrderCap * 2 +
            2 * kDepthBins * 4 + 32;
 }
 
@@ -90,7 +91,7 @@ void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const
 // Fills dispatch[n_items] with the item indices in launch order (costliest first within each die's share).
 constexpr uint32_t kMaxPlannedItems = 16384;   // k_dispatch_order keeps one cost word per item in LDS
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
-                 uint32_t n_items, uint32_t* cost, uint32_t* dispatch);
+                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch);
 hipError_t prepare_raster(int threads, size_t lds);
 void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
                   const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb);

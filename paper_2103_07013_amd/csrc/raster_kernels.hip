@@ -23,7 +23,7 @@ struct WaveLds {
 };
 
 // One lane per queued small triangle: at most kSmallMax pixel centres each.
-__device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u64* vis, int W,
+__device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u64* vis, const Window& win,
                                             const BPS_GLOBAL uint32_t* ctri_id) {
     bool have = lane < n;
     // the queue holds the triangle's slot in the cluster arrays; its id is fetched here, one
@@ -42,7 +42,7 @@ __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u
     for (int k = 0; k < kSmallMax; ++k) {
         bool act = k < cnt;
         if (ballot64(act) == 0) break;
-        shade_pixel(s, i, j, act, id, vis, W);
+        shade_pixel(s, i, j, act, id, vis, win);
         ++i;
         if (i >= i_lo + nx) { i = i_lo; ++j; }
     }
@@ -51,7 +51,8 @@ __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u
 // Append small triangles to the wave's queue; whenever it reaches 64 entries, drain them.
 __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool want, uint32_t xy0, uint32_t xy1,
                                            uint32_t xy2, float iw0, float iw1, float iw2, uint32_t ref, uint32_t box,
-                                           int lane, u64* vis, int W, const BPS_GLOBAL uint32_t* ctri_id) {
+                                           int lane, u64* vis, const Window& win,
+                                           const BPS_GLOBAL uint32_t* ctri_id) {
     u64 mask = ballot64(want);
     if (mask == 0) return;
     int n = __popcll(mask);
@@ -68,7 +69,7 @@ __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool wa
     }
     if (n >= room) {
         wave_lds_sync();
-        drain_small(L, 64, lane, vis, W, ctri_id);
+        drain_small(L, 64, lane, vis, win, ctri_id);
         wave_lds_sync();
         pos -= 64;
         if (later) {
@@ -86,7 +87,7 @@ __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool wa
 // Whole wavefront on one large triangle: 8x8 pixel blocks over its bounding box.
 __device__ __forceinline__ void raster_large(uint32_t xy0, uint32_t xy1, uint32_t xy2, float iw0, float iw1, float iw2,
                                              uint32_t id, int i_lo, int i_hi, int j_lo, int j_hi, int lane, u64* vis,
-                                             int W) {
+                                             const Window& win) {
     Setup s = make_setup(xy0, xy1, xy2, iw0, iw1, iw2);
     int li = lane & 7, lj = lane >> 3;
     for (int by = j_lo >> 3; by <= (j_hi >> 3); ++by) {
@@ -95,7 +96,7 @@ __device__ __forceinline__ void raster_large(uint32_t xy0, uint32_t xy1, uint32_
         for (int bx = i_lo >> 3; bx <= (i_hi >> 3); ++bx) {
             int i = (bx << 3) + li;
             bool act = jok && i >= i_lo && i <= i_hi;
-            shade_pixel(s, i, j, act, id, vis, W);
+            shade_pixel(s, i, j, act, id, vis, win);
         }
     }
 }
@@ -107,17 +108,17 @@ __device__ __forceinline__ uint32_t as_u32(short2v v) { return __builtin_bit_cas
 // Pixel centres inside a triangle's bounding box, both axes at once with packed 16-bit
 // arithmetic.  Pixel i has its centre at 256 (i - 64) + 128 in packed coordinates, so the first
 // centre at or right of x is (x + 127) >> 8 and the last centre at or left of x is (x - 128) >> 8
-// (both minus 64).  Returns false when the box, clamped to the frame, holds no centre; otherwise
-// lo = first pixel - 64 and ext = last - first per axis.
-__device__ __forceinline__ bool centre_box(uint32_t xy0, uint32_t xy1, uint32_t xy2, int H, int W, short2v& lo,
+// (both minus 64).  Returns false when the box, clamped to the work-group's window of the frame,
+// holds no centre; otherwise lo = first pixel - 64 and ext = last - first per axis.
+__device__ __forceinline__ bool centre_box(uint32_t xy0, uint32_t xy1, uint32_t xy2, const Window& win, short2v& lo,
                                            short2v& ext) {
     short2v a = as_s2(xy0), b = as_s2(xy1), c = as_s2(xy2);
     short2v mn = __builtin_elementwise_min(a, __builtin_elementwise_min(b, c));
     short2v mx = __builtin_elementwise_max(a, __builtin_elementwise_max(b, c));
     lo = (mn + (short)127) >> (short)8;
     short2v hi = (mx - (short)128) >> (short)8;
-    short2v lo_clamp = {(short)-64, (short)-64};
-    short2v hi_clamp = {(short)(W - 65), (short)(H - 65)};
+    short2v lo_clamp = {(short)(win.x0 - 64), (short)(win.y0 - 64)};
+    short2v hi_clamp = {(short)(win.x0 + win.w - 65), (short)(win.y0 + win.h - 65)};
     lo = __builtin_elementwise_max(lo, lo_clamp);
     hi = __builtin_elementwise_min(hi, hi_clamp);
     ext = hi - lo;                              // both halves >= 0: some pixel centre is inside
@@ -129,14 +130,15 @@ __device__ __forceinline__ bool centre_box(uint32_t xy0, uint32_t xy1, uint32_t 
 // carry it through the queue, only large ones look the id up here.
 __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool valid, short2v lo, short2v ext,
                                      uint32_t xy0, uint32_t xy1, uint32_t xy2, float iw0, float iw1, float iw2,
-                                     uint32_t ref, const BPS_GLOBAL uint32_t* ctri_id, int lane, u64* vis, int W) {
+                                     uint32_t ref, const BPS_GLOBAL uint32_t* ctri_id, int lane, u64* vis,
+                                     const Window& win) {
     u64 vmask = ballot64(valid);
     if (vmask == 0) return;
     int nx = (int)ext.x + 1, ny = (int)ext.y + 1;
     int i_lo = (int)lo.x + 64, j_lo = (int)lo.y + 64;
     bool small = valid && nx * ny <= kSmallMax;
     uint32_t box = (uint32_t)i_lo | ((uint32_t)j_lo << 8) | ((uint32_t)nx << 16) | ((uint32_t)ny << 24);
-    push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, W, ctri_id);
+    push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, win, ctri_id);
     u64 big = ballot64(valid && !small);
     const uint32_t id = (valid && !small) ? ctri_id[ref] : 0u;
     while (big) {
@@ -145,33 +147,43 @@ __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool va
         int bi = bcast_i(i_lo, src), bj = bcast_i(j_lo, src);
         raster_large((uint32_t)bcast_i((int)xy0, src), (uint32_t)bcast_i((int)xy1, src), (uint32_t)bcast_i((int)xy2, src),
                      bcast_f(iw0, src), bcast_f(iw1, src), bcast_f(iw2, src), (uint32_t)bcast_i((int)id, src), bi,
-                     bi + bcast_i(nx, src) - 1, bj, bj + bcast_i(ny, src) - 1, lane, vis, W);
+                     bi + bcast_i(nx, src) - 1, bj, bj + bcast_i(ny, src) - 1, lane, vis, win);
     }
 }
 
-// Conservative test of an axis-aligned box against the six frustum planes of M, in world
-// space.  For plane (row3 +- rowk) . (v, 1) >= 0 the largest value over the box is compared
-// with a negative margin proportional to the magnitude of the terms, so that rounding in this
-// test and in the per-vertex transform can never cull a box holding a vertex the exact rule
-// keeps.  NaNs compare false and therefore never cull.
-__device__ __forceinline__ bool box_outside_frustum(const float (&M)[16], float lx, float ly, float lz, float hx,
-                                                    float hy, float hz) {
+// Conservative test of an axis-aligned box against the planes that bound the work-group's window
+// of the frame, in world space: near z >= 0, far w - z >= 0 and the four side planes
+// x - aL w >= 0, aR w - x >= 0, y - aT w >= 0, aB w - y >= 0 (aL = -1, aR = +1 for a whole frame,
+// i.e. w + x >= 0 and w - x >= 0).  For each plane the largest value over the box is compared with a
+// negative margin proportional to the magnitude of the terms, so that rounding in this test and
+// in the per-vertex transform can never cull a box holding a vertex the exact rule keeps; window
+// edges lie half a pixel outside the outermost pixel centres, far more than vertex snapping moves
+// anything.  NaNs compare false and therefore never cull.
+__device__ __forceinline__ bool box_outside_frustum(const float (&M)[16], const Window& win, float lx, float ly,
+                                                    float lz, float hx, float hy, float hz) {
     const float eps = 1.52587890625e-05f;   // 2^-16
     float ax = fmaxf(fabsf(lx), fabsf(hx)), ay = fmaxf(fabsf(ly), fabsf(hy)), az = fmaxf(fabsf(lz), fabsf(hz));
     bool outside = false;
 #pragma unroll
     for (int k = 0; k < 6; ++k) {
-        const int r = (k < 2) ? 0 : (k < 4) ? 1 : 2;
         float px, py, pz, pw, qx, qy, qz, qw;   // plane coefficients and their magnitudes
         if (k == 4) {
             px = M[8]; py = M[9]; pz = M[10]; pw = M[11];
             qx = fabsf(px); qy = fabsf(py); qz = fabsf(pz); qw = fabsf(pw);
+        } else if (k == 5) {
+            px = M[12] - M[8]; py = M[13] - M[9]; pz = M[14] - M[10]; pw = M[15] - M[11];
+            qx = fabsf(M[12]) + fabsf(M[8]); qy = fabsf(M[13]) + fabsf(M[9]);
+            qz = fabsf(M[14]) + fabsf(M[10]); qw = fabsf(M[15]) + fabsf(M[11]);
         } else {
+            const int r = (k < 2) ? 0 : 1;
+            // (row_r - a row_3) for the low side, (a row_3 - row_r) for the high side
+            const float a = k == 0 ? win.aL : k == 1 ? win.aR : k == 2 ? win.aT : win.aB;
             const float sg = (k == 0 || k == 2) ? 1.0f : -1.0f;
-            px = M[12] + sg * M[4 * r + 0]; py = M[13] + sg * M[4 * r + 1];
-            pz = M[14] + sg * M[4 * r + 2]; pw = M[15] + sg * M[4 * r + 3];
-            qx = fabsf(M[12]) + fabsf(M[4 * r + 0]); qy = fabsf(M[13]) + fabsf(M[4 * r + 1]);
-            qz = fabsf(M[14]) + fabsf(M[4 * r + 2]); qw = fabsf(M[15]) + fabsf(M[4 * r + 3]);
+            px = sg * (M[4 * r + 0] - a * M[12]); py = sg * (M[4 * r + 1] - a * M[13]);
+            pz = sg * (M[4 * r + 2] - a * M[14]); pw = sg * (M[4 * r + 3] - a * M[15]);
+            const float aa = fabsf(a);
+            qx = fabsf(M[4 * r + 0]) + aa * fabsf(M[12]); qy = fabsf(M[4 * r + 1]) + aa * fabsf(M[13]);
+            qz = fabsf(M[4 * r + 2]) + aa * fabsf(M[14]); qw = fabsf(M[4 * r + 3]) + aa * fabsf(M[15]);
         }
         float dmax = pw + fmaxf(px * lx, px * hx) + fmaxf(py * ly, py * hy) + fmaxf(pz * lz, pz * hz);
         float mag = fmaf(qx, ax, fmaf(qy, ay, fmaf(qz, az, qw)));
@@ -191,8 +203,9 @@ constexpr uint32_t kNoPixel = 0xFFFFFFFFu;   // box_footprint: the box cannot co
 // may reach the eye plane, or is more than 8 pixels wide or high):
 //   bit 0 testable | x0 7 bits | y0 7 bits | width-1 3 bits | height-1 3 bits | top 19 bits of the
 //   w bound (truncated, i.e. rounded towards the eye)
-__device__ __forceinline__ uint32_t box_footprint(const float (&M)[16], const FrameParams& fp, float lx, float ly,
-                                                 float lz, float hx, float hy, float hz, uint32_t& wbits19) {
+__device__ __forceinline__ uint32_t box_footprint(const float (&M)[16], const FrameParams& fp, const Window& win,
+                                                 float lx, float ly, float lz, float hx, float hy, float hz,
+                                                 uint32_t& wbits19) {
     const float eps = 1.52587890625e-05f;   // 2^-16
     wbits19 = 0u;
     float ax = fmaxf(fabsf(lx), fabsf(hx)), ay = fmaxf(fabsf(ly), fabsf(hy)), az = fmaxf(fabsf(lz), fabsf(hz));
@@ -218,8 +231,8 @@ __device__ __forceinline__ uint32_t box_footprint(const float (&M)[16], const Fr
     float fx0 = ceilf(fmaf(x0, hw, hw) - 0.5f - slack), fx1 = floorf(fmaf(x1, hw, hw) - 0.5f + slack);
     float fy0 = ceilf(fmaf(y0, hh, hh) - 0.5f - slack), fy1 = floorf(fmaf(y1, hh, hh) - 0.5f + slack);
     if (!(fx0 == fx0 && fx1 == fx1 && fy0 == fy0 && fy1 == fy1)) return 0u;   // NaN somewhere: no bound
-    fx0 = fmaxf(fx0, 0.0f); fy0 = fmaxf(fy0, 0.0f);
-    fx1 = fminf(fx1, (float)(fp.W - 1)); fy1 = fminf(fy1, (float)(fp.H - 1));
+    fx0 = fmaxf(fx0, (float)win.x0); fy0 = fmaxf(fy0, (float)win.y0);
+    fx1 = fminf(fx1, (float)(win.x0 + win.w - 1)); fy1 = fminf(fy1, (float)(win.y0 + win.h - 1));
     if (fx0 > fx1 || fy0 > fy1) return kNoPixel;
     int ix0 = (int)fx0, ix1 = (int)fx1, iy0 = (int)fy0, iy1 = (int)fy1;
     int bw = ix1 - ix0, bh = iy1 - iy0;
@@ -238,7 +251,8 @@ __device__ __forceinline__ int depth_bin(u64 e) {
 
 // One lane per queued straddling triangle: clip, project, fan, hand the pieces to emit().
 __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, int& small_count, const SceneDev& sc,
-                                           const float (&M)[16], const FrameParams& fp, int lane, u64* vis) {
+                                           const float (&M)[16], const FrameParams& fp, const Window& win, int lane,
+                                           u64* vis) {
     bool have = lane < n;
     uint32_t ref = have ? L.clipq[first + lane] : 0u;
     uint32_t c = ref >> 7, slot = ref & 127u;
@@ -301,8 +315,8 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
         uint32_t a = v ? pxy[0] : 0u, b = v ? pxy[i] : 0u, d = v ? pxy[i + 1] : 0u;
         float wa = v ? piw[0] : 0.0f, wb = v ? piw[i] : 0.0f, wd = v ? piw[i + 1] : 0.0f;
         short2v lo, ext;
-        const bool has = centre_box(a, b, d, fp.H, fp.W, lo, ext);
-        emit(L, small_count, v && has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, fp.W);
+        const bool has = centre_box(a, b, d, win, lo, ext);
+        emit(L, small_count, v && has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, win);
     }
 }
 
@@ -319,7 +333,7 @@ __device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool wan
 
 // =============================================================================================
 template <int NT>
-__global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
+__global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
                                                uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats,
@@ -329,7 +343,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int HW = fp.H * fp.W;
+    const int HW = fp.tile_w * fp.tile_h;      // LDS is sized for a full tile; edge tiles may be smaller
 
     u64* vis = reinterpret_cast<u64*>(smem);
     unsigned char* wbase = smem + (size_t)HW * 8 + (size_t)wave * kWaveLdsBytes;
@@ -358,7 +372,19 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
 #pragma unroll
     for (int k = 0; k < 16; ++k) M[k] = view_proj[(size_t)item.env * 16 + k];
 
-    for (int p = tid; p < HW; p += NT) vis[p] = kEmptyKey;
+    // this work-group's window of the frame
+    const int tiles_x = (fp.W + fp.tile_w - 1) / fp.tile_w;
+    Window win;
+    win.x0 = (int)(item.tile % (uint32_t)tiles_x) * fp.tile_w;
+    win.y0 = (int)(item.tile / (uint32_t)tiles_x) * fp.tile_h;
+    win.w = min(fp.tile_w, fp.W - win.x0);
+    win.h = min(fp.tile_h, fp.H - win.y0);
+    win.aL = 2.0f * (float)win.x0 / (float)fp.W - 1.0f;
+    win.aR = 2.0f * (float)(win.x0 + win.w) / (float)fp.W - 1.0f;
+    win.aT = 2.0f * (float)win.y0 / (float)fp.H - 1.0f;
+    win.aB = 2.0f * (float)(win.y0 + win.h) / (float)fp.H - 1.0f;
+    const int npix = win.w * win.h;
+    for (int p = tid; p < npix; p += NT) vis[p] = kEmptyKey;
 
     int small_count = 0, clip_count = 0;
     // diagnostics (only when the host passes a counter block): per-wave tallies, one atomic each at the end
@@ -375,9 +401,9 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     const BPS_GLOBAL uint32_t* g_ctris = gptr(sc.ctris);
     const BPS_GLOBAL uint32_t* g_ctri_id = gptr(sc.ctri_id);
     const BPS_GLOBAL float* g_bounds = gptr(sc.cbounds);
-    const uint32_t S = item.n_splits;
+    const uint32_t S = item.split_of >> 16, item_split = item.split_of & 0xFFFFu;
     const uint32_t nblocks_total = (sc.n_clusters + 63u) / 64u;
-    const uint32_t nb_item = nblocks_total > item.split ? (nblocks_total - item.split + S - 1u) / S : 0u;
+    const uint32_t nb_item = nblocks_total > item_split ? (nblocks_total - item_split + S - 1u) / S : 0u;
     const BPS_GLOBAL float* g_bbounds = gptr(sc.bbounds);
     const bool occlusion = fp.cull > 1;
     const uint32_t* vis_hi = reinterpret_cast<const uint32_t*>(vis) + 1;   // depth word of pixel p is vis_hi[2 p]
@@ -391,7 +417,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
         // sortable integer so that any bit pattern, NaN included, has a unique rank
         uint32_t* keys = reinterpret_cast<uint32_t*>(list);
         for (uint32_t b = tid; b < nb_item; b += NT) {
-            const uint32_t gb = b * S + item.split;
+            const uint32_t gb = b * S + item_split;
             float wmin = M[15];
 #pragma unroll
             for (int a = 0; a < 3; ++a) {
@@ -407,7 +433,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 lo[a] = g_bbounds[(size_t)a * sc.b_stride + gb];
                 hi[a] = g_bbounds[(size_t)(a + 3) * sc.b_stride + gb];
             }
-            if (box_outside_frustum(M, lo[0], lo[1], lo[2], hi[0], hi[1], hi[2])) key = 0xFFFFFFFFu;
+            if (box_outside_frustum(M, win, lo[0], lo[1], lo[2], hi[0], hi[1], hi[2])) key = 0xFFFFFFFFu;
             else atomicAdd(blocks_in_view, 1u);
             keys[b] = key;
         }
@@ -451,7 +477,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 break;
             }
             const uint32_t jb = sorted ? (uint32_t)order[blk] : blk;
-            const uint32_t cl = (jb * S + item.split) * 64u + (uint32_t)lane;
+            const uint32_t cl = (jb * S + item_split) * 64u + (uint32_t)lane;
             bool visible = cl < sc.n_clusters;
             uint32_t foot = 0u, wb19 = 0u;
             st_tested += (uint32_t)__popcll(ballot64(visible));
@@ -460,9 +486,9 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 float lx = g_bounds[cc], ly = g_bounds[sc.c_stride + cc], lz = g_bounds[2 * sc.c_stride + cc];
                 float hx = g_bounds[3 * sc.c_stride + cc], hy = g_bounds[4 * sc.c_stride + cc],
                       hz = g_bounds[5 * sc.c_stride + cc];
-                visible = visible && !box_outside_frustum(M, lx, ly, lz, hx, hy, hz);
+                visible = visible && !box_outside_frustum(M, win, lx, ly, lz, hx, hy, hz);
                 if (occlusion && visible) {
-                    foot = box_footprint(M, fp, lx, ly, lz, hx, hy, hz, wb19);
+                    foot = box_footprint(M, fp, win, lx, ly, lz, hx, hy, hz, wb19);
                     visible = foot != kNoPixel;
                 }
             }
@@ -526,7 +552,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                     const uint32_t wbits = (hi32 >> 13) << 12;
                     const int qx = lane & 7, qy = lane >> 3;
                     const bool in = qx <= bw && qy <= bh;
-                    const uint32_t d = in ? vis_hi[2 * ((fy + qy) * fp.W + fx + qx)] : 0u;
+                    const uint32_t d = in ? vis_hi[2 * ((fy - win.y0 + qy) * win.w + fx - win.x0 + qx)] : 0u;
                     if (ballot64(in && d >= wbits) == 0) { ++st_hidden; continue; }
                 }
                 const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
@@ -577,8 +603,7 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 float2 a = L.stage[i0], b = L.stage[i1], d = L.stage[i2];
                 bool fast = slot * 64 + lane < ntri;
                 short2v lo, ext;
-                const bool has = centre_box(__float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), fp.H, fp.W,
-                                            lo, ext);
+                const bool has = centre_box(__float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), win, lo, ext);
                 if (!all_inside) {
                     uint32_t oa = L.stage_oc[i0], ob = L.stage_oc[i1], od = L.stage_oc[i2];
                     uint32_t o_or = oa | ob | od, o_and = oa & ob & od;
@@ -592,12 +617,12 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
                 }
                 emit(L, small_count, fast && has, lo, ext, __float_as_uint(a.x), __float_as_uint(b.x),
                      __float_as_uint(d.x), a.y, b.y, d.y, c * 128u + (uint32_t)(slot * 64 + lane), g_ctri_id, lane, vis,
-                     fp.W);
+                     win);
             }
             // ---- clip queue: full wavefronts only while streaming
             while (clip_count >= 64) {
                 wave_lds_sync();
-                drain_clip(L, clip_count - 64, 64, small_count, sc, M, fp, lane, vis);
+                drain_clip(L, clip_count - 64, 64, small_count, sc, M, fp, win, lane, vis);
                 clip_count -= 64;
             }
         }
@@ -609,11 +634,11 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     }
     if (clip_count > 0) {
         wave_lds_sync();
-        drain_clip(L, 0, clip_count, small_count, sc, M, fp, lane, vis);
+        drain_clip(L, 0, clip_count, small_count, sc, M, fp, win, lane, vis);
     }
     if (small_count > 0) {
         wave_lds_sync();
-        drain_small(L, small_count, lane, vis, fp.W, g_ctri_id);
+        drain_small(L, small_count, lane, vis, win, g_ctri_id);
     }
     // diagnostics: per-wave tallies go through LDS (the survivor list is free by now) and leave as
     // one record of 16 words per work-group, without atomics
@@ -633,18 +658,17 @@ __global__ __launch_bounds__(NT) void k_raster(const SceneDev* __restrict__ scen
     }
 
     // ---- resolve this work-group's frame
-    const size_t base = (size_t)item.env * HW;
-    if (fp.merge) {
-        for (int p = tid; p < HW; p += NT) {
-            u64 key = vis[p];
-            if (key != kEmptyKey) atomicMin(&gvis[base + p], key);
-        }
-    } else {
-        for (int p = tid; p < HW; p += NT) {
-            u64 key = vis[p];
-            bool hit = key != kEmptyKey;
-            out_depth[base + p] = hit ? __uint_as_float((uint32_t)(key >> 32)) : fp.background;
-            if (out_id) out_id[base + p] = hit ? (uint32_t)key : 0xFFFFFFFFu;
+    const size_t base = (size_t)item.env * fp.H * fp.W;
+    for (int p = tid; p < npix; p += NT) {
+        const int y = p / win.w, x = p - y * win.w;
+        const size_t o = base + (size_t)(win.y0 + y) * fp.W + (size_t)(win.x0 + x);
+        const u64 key = vis[p];
+        const bool hit = key != kEmptyKey;
+        if (fp.merge) {
+            if (hit) atomicMin(&gvis[o], key);
+        } else {
+            out_depth[o] = hit ? __uint_as_float((uint32_t)(key >> 32)) : fp.background;
+            if (out_id) out_id[o] = hit ? (uint32_t)key : 0xFFFFFFFFu;
         }
     }
 }
@@ -668,7 +692,7 @@ __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float
 // environment's frustum; k_dispatch_order then ranks the items of each die's share (index % 8)
 // by decreasing cost.
 __global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
-                                                  const float* __restrict__ view_proj, uint32_t n_items,
+                                                  const float* __restrict__ view_proj, FrameParams fp, uint32_t n_items,
                                                   uint32_t* __restrict__ cost) {
     const uint32_t i = blockIdx.x;
     if (i >= n_items) return;
@@ -679,11 +703,22 @@ __global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ s
     for (int k = 0; k < 16; ++k) M[k] = view_proj[(size_t)item.env * 16 + k];
     const BPS_GLOBAL float* bb = gptr(sc.bbounds);
     const uint32_t nblocks = (sc.n_clusters + 63u) / 64u;
+    const uint32_t S = item.split_of >> 16, item_split = item.split_of & 0xFFFFu;
+    const int tiles_x = (fp.W + fp.tile_w - 1) / fp.tile_w;
+    Window win;
+    win.x0 = (int)(item.tile % (uint32_t)tiles_x) * fp.tile_w;
+    win.y0 = (int)(item.tile / (uint32_t)tiles_x) * fp.tile_h;
+    win.w = min(fp.tile_w, fp.W - win.x0);
+    win.h = min(fp.tile_h, fp.H - win.y0);
+    win.aL = 2.0f * (float)win.x0 / (float)fp.W - 1.0f;
+    win.aR = 2.0f * (float)(win.x0 + win.w) / (float)fp.W - 1.0f;
+    win.aT = 2.0f * (float)win.y0 / (float)fp.H - 1.0f;
+    win.aB = 2.0f * (float)(win.y0 + win.h) / (float)fp.H - 1.0f;
     uint32_t count = 0;
-    for (uint32_t gb = item.split + item.n_splits * threadIdx.x; gb < nblocks; gb += item.n_splits * 64u) {
+    for (uint32_t gb = item_split + S * threadIdx.x; gb < nblocks; gb += S * 64u) {
         float lx = bb[gb], ly = bb[sc.b_stride + gb], lz = bb[2 * sc.b_stride + gb];
         float hx = bb[3 * sc.b_stride + gb], hy = bb[4 * sc.b_stride + gb], hz = bb[5 * sc.b_stride + gb];
-        count += box_outside_frustum(M, lx, ly, lz, hx, hy, hz) ? 0u : 1u;
+        count += box_outside_frustum(M, win, lx, ly, lz, hx, hy, hz) ? 0u : 1u;
     }
 #pragma unroll
     for (int sh = 32; sh >= 1; sh >>= 1) count += (uint32_t)__shfl_xor((int)count, sh, 64);
@@ -707,8 +742,8 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
 }
 
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
-                 uint32_t n_items, uint32_t* cost, uint32_t* dispatch) {
-    hipLaunchKernelGGL(k_item_cost, dim3(n_items), dim3(64), 0, stream, scenes, items, view_proj, n_items, cost);
+                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch) {
+    hipLaunchKernelGGL(k_item_cost, dim3(n_items), dim3(64), 0, stream, scenes, items, view_proj, fp, n_items, cost);
     hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), n_items * sizeof(uint32_t), stream, cost, n_items, dispatch);
 }
 
