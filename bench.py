@@ -92,6 +92,64 @@ def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=
     return res
 
 
+def rotation_run(bps, torch, w, steps, warmup):
+    """Render while a loader thread keeps replacing scenes (asynchronous uploads on a side stream,
+    retired scenes recycled): the paper's continuous rotation of the K resident assets (Sec. 3.2)."""
+    import threading
+    import synth
+    r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W)
+    K = len(w.scenes)
+    handles = [r.load_scene(s.vertices, s.indices) for s in w.scenes]
+    spare = [synth.make_multiroom_scene(w.scenes[0].T, seed=1500 + k) for k in range(2)]
+    pool = list(w.scenes) + spare
+    state = {"ids": np.array([handles[k] for k in w.scene_ids], np.int32), "stop": False, "loaded": 0, "load_s": 0.0}
+    lock = threading.Lock()
+    copy_stream = torch.cuda.Stream()
+    vp = torch.from_numpy(w.view_proj).cuda()
+    depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def loader():
+        slot_handles = list(handles)
+        n = 0
+        while not state["stop"]:
+            k = n % K                                   # scene slot to replace
+            mesh = pool[(n + K) % len(pool)]
+            t0 = time.perf_counter()
+            new = bps.bps_load_scene_async(r.handle, mesh.vertices, mesh.indices, None, copy_stream)
+            state["load_s"] += time.perf_counter() - t0
+            old = slot_handles[k]
+            slot_handles[k] = new
+            with lock:
+                state["ids"] = np.array([slot_handles[j] for j in w.scene_ids], np.int32)
+            bps.bps_unload_scene(r.handle, old)         # requests that still use it are queued: allowed
+            state["loaded"] += 1
+            n += 1
+
+    for _ in range(warmup):
+        bps.bps_render(r.handle, state["ids"], vp, depth, stream=stream)
+    torch.cuda.synchronize()
+    th = threading.Thread(target=loader)
+    th.start()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        with lock:
+            ids = state["ids"]
+        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    state["stop"] = True
+    th.join()
+    torch.cuda.synchronize()
+    out = {"frames_per_s": w.B * steps / dt, "steps": steps, "scenes_loaded_meanwhile": state["loaded"],
+           "host_ms_per_load": 1e3 * state["load_s"] / max(1, state["loaded"]),
+           "device_blocks_allocated": bps.bps_query(r.handle, 0, 8),
+           "note": "one loader thread replaces scenes back to back (cluster packing on the host, copy on a side stream) "
+                   "while the render thread issues requests; every request after a swap uses the new scene"}
+    r.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -104,6 +162,7 @@ def main():
     ap.add_argument("--no-cull", action="store_true", help="stream every cluster (no culling of clusters)")
     ap.add_argument("--no-occlusion", action="store_true", help="frustum culling of clusters only")
     ap.add_argument("--no-dispatch-order", action="store_true", help="launch work-groups in batch order")
+    ap.add_argument("--rotate", action="store_true", help="also time rendering while scenes are being replaced")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed run: no diagnostics request, no full-stream run (for profiler runs)")
     ap.add_argument("--cpu-envs", type=int, default=512, help="environments in the oracle timing sample (0 = skip)")
@@ -212,6 +271,8 @@ def main():
         rl["frames_per_s"] = w.B * steps2 / fs["dt"]
         rl["launches_timed"] = fs["launches"]
         out["roofline_full_stream"] = rl
+    if args.rotate and not w.rgbd:
+        out["rotation"] = rotation_run(bps, torch, w, max(2000, args.steps), args.warmup)
     if args.cpu_envs > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_envs)
     print(json.dumps(out))

@@ -16,8 +16,11 @@
  *   minimum of (depth bits << 32 | triangle id), i.e. nearest surface, ties to the lower id.
  *
  * All functions return a status; none throws or aborts.  Unless stated otherwise pointers are
- * HOST memory.  A renderer must be driven by one thread at a time; different renderers are
- * independent.  There is no CPU fallback: without a usable GPU bps_create fails.
+ * HOST memory.  bps_render, the scene calls and bps_scene_ready may be called from different
+ * threads (typically one render thread and one loader thread; the library serialises its
+ * bookkeeping and keeps the long host-side part of a load outside the lock); everything else
+ * must not overlap other calls on the same renderer.  Different renderers are independent.
+ * There is no CPU fallback: without a usable GPU bps_create fails.
  */
 #ifndef BPS_H
 #define BPS_H
@@ -81,6 +84,18 @@ void bps_destroy(bps_renderer *r);
 bps_status bps_load_scene(bps_renderer *r, const float *vertices, uint32_t V, const uint32_t *indices, uint32_t T,
                           const uint8_t *colors, bps_scene *out_handle);
 
+/* Asynchronous scene upload (Sec. 3.2: new scenes are streamed into GPU memory while rollouts
+ * and learning continue, and scenes no longer referenced are dropped).  Same arguments and
+ * host-side work (validation, re-packing into a pinned image) as bps_load_scene, but the copy to
+ * the device is only enqueued on `copy_stream` (a hipStream_t other than the render stream) and the
+ * call returns without waiting; the caller's arrays may be freed on return.  The handle may be
+ * passed to bps_render at once: a request that references a scene still in flight is ordered
+ * after its copy on the device, the host never blocks.  bps_scene_ready reports (without
+ * waiting) whether the copy has finished. */
+bps_status bps_load_scene_async(bps_renderer *r, const float *vertices, uint32_t V, const uint32_t *indices,
+                                uint32_t T, const uint8_t *colors, void *copy_stream, bps_scene *out_handle);
+bps_status bps_scene_ready(bps_renderer *r, bps_scene scene, int32_t *ready);
+
 /* Host-only helper (no GPU needed): re-pack a mesh exactly as bps_load_scene does and copy the
  * cluster arrays out, for tests and tools.  On entry *count is the capacity of the output
  * arrays in clusters (ignored when all three are NULL); on return it is the cluster count.
@@ -90,7 +105,9 @@ bps_status bps_load_scene(bps_renderer *r, const float *vertices, uint32_t V, co
 bps_status bps_pack_clusters(const float *vertices, uint32_t V, const uint32_t *indices, uint32_t T, uint32_t *count,
                              float *verts_out, uint32_t *tris_out, uint32_t *ids_out);
 
-/* Frees a scene.  The caller must not unload a scene that queued renders still use. */
+/* Retires a scene.  Safe while requests that reference it are still queued: its device block and
+ * table slot are only reused after those requests have finished (no host wait).  The handle is
+ * invalid for new requests from this call on. */
 bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 
 /* One batched render request (Sec. 3: the whole batch of N environment states is rendered at
@@ -132,7 +149,8 @@ bps_status bps_read_diagnostics(bps_renderer *r, uint64_t *out, uint32_t capacit
 /* Facts about a loaded scene and the launch plan, for benchmarks and tests.
  * what: 0 = clusters in the scene, 1 = triangles, 2 = vertices, 3 = device bytes held,
  *       4 = splits used by the last request, 5 = work-groups of the last request,
- *       6 = work-group size, 7 = LDS bytes per work-group. */
+ *       6 = work-group size, 7 = LDS bytes per work-group, 8 = device blocks allocated for scenes so
+ *       far, 9 = retired scene blocks waiting for reuse. */
 bps_status bps_query(bps_renderer *r, bps_scene scene, int32_t what, uint64_t *value);
 
 /* Text of the last error on this renderer (owned by the renderer; never NULL).

@@ -12,7 +12,7 @@ MODE_DEPTH, MODE_RGBD = 0, 1
 FLAG_NO_CLUSTER_CULL = 1
 FLAG_NO_OCCLUSION_CULL = 2
 FLAG_NO_DISPATCH_ORDER = 4
-EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
+EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
            "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 
 
@@ -46,6 +46,10 @@ def load_library():
     lib.bps_destroy.argtypes = [vp]
     lib.bps_load_scene.restype = ctypes.c_int32
     lib.bps_load_scene.argtypes = [vp, vp, ctypes.c_uint32, vp, ctypes.c_uint32, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.bps_load_scene_async.restype = ctypes.c_int32
+    lib.bps_load_scene_async.argtypes = [vp, vp, ctypes.c_uint32, vp, ctypes.c_uint32, vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.bps_scene_ready.restype = ctypes.c_int32
+    lib.bps_scene_ready.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.bps_pack_clusters.restype = ctypes.c_int32
     lib.bps_pack_clusters.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32), vp, vp, vp]
     lib.bps_unload_scene.restype = ctypes.c_int32
@@ -104,6 +108,25 @@ def bps_load_scene(handle, vertices, indices, colors=None):
     _check(lib.bps_load_scene(handle, v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0],
                               None if c is None else c.ctypes.data, ctypes.byref(out)), handle)
     return int(out.value)
+
+
+def bps_load_scene_async(handle, vertices, indices, colors=None, copy_stream=None):
+    """Like bps_load_scene but only enqueues the device copy on copy_stream (torch stream or raw handle)."""
+    lib = load_library()
+    v = np.ascontiguousarray(vertices, np.float32).reshape(-1, 3)
+    i = np.ascontiguousarray(indices, np.uint32).reshape(-1, 3)
+    c = None if colors is None else np.ascontiguousarray(colors, np.uint8).reshape(-1, 3)
+    s = copy_stream if isinstance(copy_stream, int) or copy_stream is None else copy_stream.cuda_stream
+    out = ctypes.c_int32(-1)
+    _check(lib.bps_load_scene_async(handle, v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0],
+                                    None if c is None else c.ctypes.data, ctypes.c_void_p(s or 0), ctypes.byref(out)), handle)
+    return int(out.value)
+
+
+def bps_scene_ready(handle, scene):
+    flag = ctypes.c_int32(0)
+    _check(load_library().bps_scene_ready(handle, int(scene), ctypes.byref(flag)), handle)
+    return bool(flag.value)
 
 
 def bps_pack_clusters(vertices, indices):
@@ -212,6 +235,9 @@ class Renderer:
 
     def load_scene(self, vertices, indices, colors=None):
         return bps_load_scene(self.handle, vertices, indices, colors)
+
+    def load_scene_async(self, vertices, indices, colors=None, copy_stream=None):
+        return bps_load_scene_async(self.handle, vertices, indices, colors, copy_stream)
 
     def unload_scene(self, scene):
         bps_unload_scene(self.handle, scene)

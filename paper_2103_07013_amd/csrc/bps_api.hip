@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -25,12 +26,33 @@ constexpr size_t kMaxProfiled = 4096;   // profiled requests remembered between 
 
 thread_local std::string g_create_error = "";
 
+// Device memory of one scene: a single allocation holding every array, so that loading is one
+// asynchronous copy and retiring a scene can hand the block to the next load.
+struct Arena {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+};
+
 struct HostScene {
     bool live = false;
     bps::SceneDev dev{};
-    void* allocs[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    Arena arena;
     uint64_t bytes = 0;
     bool has_colors = false;
+    hipEvent_t ready = nullptr;   // copy finished (asynchronous loads); null once known complete
+    uint64_t last_use = 0;        // sequence number of the last request that referenced the scene
+};
+
+struct Retired {      // device block or table slot that queued requests may still read
+    Arena arena;
+    int slot = -1;
+    uint64_t last_use = 0;
+};
+
+struct Staging {      // pinned host image of a scene being copied
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
 };
 
 struct RingSlot {
@@ -39,6 +61,7 @@ struct RingSlot {
     size_t capacity = 0;
     hipEvent_t done = nullptr;
     bool pending = false;
+    uint64_t seq = 0;
 };
 
 }  // namespace
@@ -55,6 +78,13 @@ struct bps_renderer {
     size_t max_lds = 0;
     std::string error = "";
     std::vector<HostScene> scenes;
+    std::vector<Retired> retired;     // waiting for the requests that used them
+    std::vector<Arena> arena_pool;    // free device blocks, reused by later loads
+    std::vector<Staging> staging;     // pinned images, reused once their copy has finished
+    hipStream_t load_stream = nullptr;   // used by the synchronous bps_load_scene
+    uint64_t seq = 0, done_seq = 0;   // requests issued / known complete
+    uint64_t arena_allocs = 0;        // device blocks allocated so far (reuse keeps this flat)
+    std::mutex mu;                    // guards all state: one loader thread may run beside the render thread
     bps::SceneDev* d_scenes = nullptr;
     RingSlot ring[kRing];
     int ring_next = 0;
@@ -94,11 +124,34 @@ bps_status fail(bps_renderer* r, bps_status code, const char* fmt, ...) {
     } while (0)
 
 void free_scene(HostScene& s) {
-    for (void*& p : s.allocs) {
-        if (p) (void)hipFree(p);
-        p = nullptr;
-    }
+    if (s.arena.ptr) (void)hipFree(s.arena.ptr);
+    if (s.ready) (void)hipEventDestroy(s.ready);
     s = HostScene{};
+}
+
+// Learn which requests have finished (never blocks) and recycle what they were holding.
+void collect(bps_renderer* r) {
+    for (RingSlot& s : r->ring)
+        if (s.pending && hipEventQuery(s.done) == hipSuccess) {
+            s.pending = false;
+            r->done_seq = std::max(r->done_seq, s.seq);
+        }
+    (void)hipGetLastError();
+    for (size_t i = 0; i < r->retired.size();) {
+        if (r->retired[i].last_use <= r->done_seq) {
+            if (r->retired[i].arena.ptr) r->arena_pool.push_back(r->retired[i].arena);
+            r->retired[i] = r->retired.back();
+            r->retired.pop_back();
+        } else {
+            ++i;
+        }
+    }
+}
+
+bool slot_busy(const bps_renderer* r, int slot) {
+    for (const Retired& x : r->retired)
+        if (x.slot == slot) return true;
+    return false;
 }
 
 bool fp_cull_enabled(const bps_renderer* r) { return !(r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL); }
@@ -198,6 +251,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
         BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
         for (RingSlot& s : r->ring) BPS_HIP(r, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+        BPS_HIP(r, hipStreamCreateWithFlags(&r->load_stream, hipStreamNonBlocking));
         return BPS_OK;
     };
     st = step();
@@ -211,6 +265,14 @@ void bps_destroy(bps_renderer* r) {
     (void)hipSetDevice(r->device);
     (void)hipDeviceSynchronize();
     for (HostScene& s : r->scenes) free_scene(s);
+    for (Retired& x : r->retired)
+        if (x.arena.ptr) (void)hipFree(x.arena.ptr);
+    for (Arena& x : r->arena_pool) (void)hipFree(x.ptr);
+    for (Staging& x : r->staging) {
+        (void)hipHostFree(x.ptr);
+        (void)hipEventDestroy(x.done);
+    }
+    if (r->load_stream) (void)hipStreamDestroy(r->load_stream);
     for (RingSlot& s : r->ring) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.dev) (void)hipFree(s.dev);
@@ -224,9 +286,13 @@ void bps_destroy(bps_renderer* r) {
     delete r;
 }
 
-bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
-                          const uint8_t* colors, bps_scene* out_handle) {
-    if (!r) return BPS_ERR_INVALID_ARG;
+namespace {
+
+// Shared by the synchronous and asynchronous entry points: validate, cluster, lay every array out
+// in one pinned image, copy it into one device block on `stream`, update the scene table on the
+// same stream and record the scene's ready event.
+bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
+                         const uint8_t* colors, hipStream_t stream, bps_scene* out_handle) {
     if (!vertices || !indices || !out_handle) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: null argument");
     if (V == 0 || T == 0) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: empty mesh (V=%u, T=%u)", V, T);
     for (size_t i = 0; i < 3 * (size_t)T; ++i)
@@ -235,14 +301,8 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
     for (size_t i = 0; i < 3 * (size_t)V; ++i)
         if (!std::isfinite(vertices[i]))
             return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: vertex %zu has a non-finite coordinate", i / 3);
-    int slot = -1;
-    for (size_t i = 0; i < r->scenes.size(); ++i)
-        if (!r->scenes[i].live) { slot = (int)i; break; }
-    if (slot < 0) {
-        if ((int)r->scenes.size() >= kMaxScenes) return fail(r, BPS_ERR_OOM, "bps_load_scene: scene table full (%d)", kMaxScenes);
-        slot = (int)r->scenes.size();
-        r->scenes.emplace_back();
-    }
+    BPS_HIP(r, hipSetDevice(r->device));
+    // the long host-side steps (clustering, filling the pinned image) run without the lock
     bps::ClusterSet cs;
     try {
         cs = bps::build_clusters(vertices, V, indices, T);
@@ -251,63 +311,166 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
     }
     if (cs.count == 0 || cs.count >= (1u << 24)) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: unsupported cluster count %u", cs.count);
 
-    BPS_HIP(r, hipSetDevice(r->device));
-    HostScene hs;
-    auto upload = [&](int k, const void* src, size_t bytes, const void** dst) -> bps_status {
-        BPS_HIP(r, hipMalloc(&hs.allocs[k], bytes));
-        BPS_HIP(r, hipMemcpy(hs.allocs[k], src, bytes, hipMemcpyHostToDevice));
-        *dst = hs.allocs[k];
-        hs.bytes += bytes;
-        return BPS_OK;
-    };
-    bps_status st;
-    const void* p = nullptr;
-    if ((st = upload(0, cs.verts.data(), cs.verts.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
-    hs.dev.cverts = (const float*)p;
-    if ((st = upload(1, cs.tris.data(), cs.tris.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
-    hs.dev.ctris = (const uint32_t*)p;
-    if ((st = upload(2, cs.tri_id.data(), cs.tri_id.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
-    hs.dev.ctri_id = (const uint32_t*)p;
-    if ((st = upload(3, vertices, (size_t)V * 12, &p)) != BPS_OK) { free_scene(hs); return st; }
-    hs.dev.verts = (const float*)p;
-    if ((st = upload(4, indices, (size_t)T * 12, &p)) != BPS_OK) { free_scene(hs); return st; }
-    hs.dev.indices = (const uint32_t*)p;
-    if (colors) {
-        if ((st = upload(5, colors, (size_t)V * 3, &p)) != BPS_OK) { free_scene(hs); return st; }
-        hs.dev.colors = (const uint8_t*)p;
-        hs.has_colors = true;
+    // ---- layout of the block (every array 256-byte aligned), scene-table record last
+    const uint32_t c_stride = (cs.count + 63u) & ~63u, nblocks = c_stride / 64u;
+    size_t off = 0;
+    auto place = [&](size_t bytes) { size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; };
+    const size_t o_cverts = place(cs.verts.size() * 4), o_ctris = place(cs.tris.size() * 4), o_ids = place(cs.tri_id.size() * 4);
+    const size_t o_verts = place((size_t)V * 12), o_idx = place((size_t)T * 12), o_col = colors ? place((size_t)V * 3) : 0;
+    const size_t o_cb = place((size_t)6 * c_stride * 4), o_bb = place((size_t)6 * nblocks * 4);
+    const size_t dev_bytes = off;
+    const size_t o_rec = place(sizeof(bps::SceneDev));
+    const size_t img_bytes = off;
+
+    // ---- pinned image: reuse one whose copy has finished, else allocate
+    Staging stg;
+    std::unique_lock<std::mutex> lock(r->mu);
+    for (size_t i = 0; i < r->staging.size(); ++i)
+        if (r->staging[i].bytes >= img_bytes && hipEventQuery(r->staging[i].done) == hipSuccess) {
+            stg = r->staging[i];
+            r->staging[i] = r->staging.back();
+            r->staging.pop_back();
+            break;
+        }
+    (void)hipGetLastError();
+    lock.unlock();
+    if (!stg.ptr) {
+        BPS_HIP(r, hipHostMalloc(&stg.ptr, img_bytes, hipHostMallocDefault));
+        stg.bytes = img_bytes;
+        hipError_t e = hipEventCreateWithFlags(&stg.done, hipEventDisableTiming);
+        if (e != hipSuccess) { (void)hipHostFree(stg.ptr); return fail(r, BPS_ERR_HIP, "bps_load_scene: %s", hipGetErrorString(e)); }
     }
-    {   // bounds as six planes of c_stride floats so that 64 lanes read 64 consecutive clusters
-        const uint32_t stride = (cs.count + 63u) & ~63u;
-        std::vector<float> planes((size_t)6 * stride, 0.0f);
+    unsigned char* img = (unsigned char*)stg.ptr;
+    std::memcpy(img + o_cverts, cs.verts.data(), cs.verts.size() * 4);
+    std::memcpy(img + o_ctris, cs.tris.data(), cs.tris.size() * 4);
+    std::memcpy(img + o_ids, cs.tri_id.data(), cs.tri_id.size() * 4);
+    std::memcpy(img + o_verts, vertices, (size_t)V * 12);
+    std::memcpy(img + o_idx, indices, (size_t)T * 12);
+    if (colors) std::memcpy(img + o_col, colors, (size_t)V * 3);
+    {   // bounds as six planes so that 64 lanes read 64 consecutive clusters (or blocks of 64 clusters)
+        float* cb = (float*)(img + o_cb);
+        float* bb = (float*)(img + o_bb);
+        std::memset(cb, 0, (size_t)6 * c_stride * 4);
         for (uint32_t c = 0; c < cs.count; ++c)
-            for (int a = 0; a < 6; ++a) planes[(size_t)a * stride + c] = cs.bounds[(size_t)c * 6 + a];
-        if ((st = upload(6, planes.data(), planes.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
-        hs.dev.cbounds = (const float*)p;
-        hs.dev.c_stride = stride;
-        // bounds of each block of 64 consecutive clusters (the unit that is depth-sorted per environment)
-        const uint32_t nblocks = stride / 64u;
-        std::vector<float> bplanes((size_t)6 * nblocks);
+            for (int k = 0; k < 6; ++k) cb[(size_t)k * c_stride + c] = cs.bounds[(size_t)c * 6 + k];
         for (uint32_t b = 0; b < nblocks; ++b)
-            for (int a = 0; a < 6; ++a) {
-                float v = cs.bounds[(size_t)b * 64 * 6 + a];
+            for (int k = 0; k < 6; ++k) {
+                float v = cs.bounds[(size_t)b * 64 * 6 + k];
                 for (uint32_t c = b * 64; c < std::min(cs.count, b * 64 + 64); ++c)
-                    v = a < 3 ? std::min(v, cs.bounds[(size_t)c * 6 + a]) : std::max(v, cs.bounds[(size_t)c * 6 + a]);
-                bplanes[(size_t)a * nblocks + b] = v;
+                    v = k < 3 ? std::min(v, cs.bounds[(size_t)c * 6 + k]) : std::max(v, cs.bounds[(size_t)c * 6 + k]);
+                bb[(size_t)k * nblocks + b] = v;
             }
-        if ((st = upload(7, bplanes.data(), bplanes.size() * 4, &p)) != BPS_OK) { free_scene(hs); return st; }
-        hs.dev.bbounds = (const float*)p;
-        hs.dev.b_stride = nblocks;
     }
+
+    // ---- table slot and device block (smallest free one that fits, else a new allocation)
+    lock.lock();
+    collect(r);
+    int slot = -1;
+    for (size_t i = 0; i < r->scenes.size(); ++i)
+        if (!r->scenes[i].live && !slot_busy(r, (int)i)) { slot = (int)i; break; }
+    if (slot < 0) {
+        if ((int)r->scenes.size() >= kMaxScenes) {
+            r->staging.push_back(stg);
+            (void)hipEventRecord(stg.done, stream);
+            return fail(r, BPS_ERR_OOM, "bps_load_scene: scene table full (%d)", kMaxScenes);
+        }
+        slot = (int)r->scenes.size();
+        r->scenes.emplace_back();
+    }
+    Arena arena;
+    int best = -1;
+    for (size_t i = 0; i < r->arena_pool.size(); ++i)
+        if (r->arena_pool[i].bytes >= dev_bytes && (best < 0 || r->arena_pool[i].bytes < r->arena_pool[best].bytes)) best = (int)i;
+    if (best >= 0) {
+        arena = r->arena_pool[best];
+        r->arena_pool[best] = r->arena_pool.back();
+        r->arena_pool.pop_back();
+    } else {
+        hipError_t e = hipMalloc(&arena.ptr, dev_bytes);
+        if (e != hipSuccess) {
+            r->staging.push_back(stg);
+            (void)hipEventRecord(stg.done, stream);
+            return fail(r, e == hipErrorOutOfMemory ? BPS_ERR_OOM : BPS_ERR_HIP, "bps_load_scene: hipMalloc(%zu): %s", dev_bytes,
+                        hipGetErrorString(e));
+        }
+        arena.bytes = dev_bytes;
+        ++r->arena_allocs;
+    }
+    unsigned char* d = (unsigned char*)arena.ptr;
+    HostScene hs;
+    hs.arena = arena;
+    hs.bytes = dev_bytes;
+    hs.has_colors = colors != nullptr;
+    hs.dev.cverts = (const float*)(d + o_cverts);
+    hs.dev.ctris = (const uint32_t*)(d + o_ctris);
+    hs.dev.ctri_id = (const uint32_t*)(d + o_ids);
+    hs.dev.verts = (const float*)(d + o_verts);
+    hs.dev.indices = (const uint32_t*)(d + o_idx);
+    hs.dev.colors = colors ? (const uint8_t*)(d + o_col) : nullptr;
+    hs.dev.cbounds = (const float*)(d + o_cb);
+    hs.dev.bbounds = (const float*)(d + o_bb);
     hs.dev.n_clusters = cs.count;
     hs.dev.n_tris = T;
     hs.dev.n_verts = V;
+    hs.dev.c_stride = c_stride;
+    hs.dev.b_stride = nblocks;
+    std::memcpy(img + o_rec, &hs.dev, sizeof(bps::SceneDev));
+
+    auto undo = [&](hipError_t e, const char* what) {
+        r->arena_pool.push_back(arena);
+        r->staging.push_back(stg);
+        (void)hipEventRecord(stg.done, stream);
+        return fail(r, BPS_ERR_HIP, "bps_load_scene: %s: %s", what, hipGetErrorString(e));
+    };
+    hipError_t e = hipMemcpyAsync(d, img, dev_bytes, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return undo(e, "mesh copy");
+    e = hipMemcpyAsync(r->d_scenes + slot, img + o_rec, sizeof(bps::SceneDev), hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return undo(e, "scene table update");
+    e = hipEventCreateWithFlags(&hs.ready, hipEventDisableTiming);
+    if (e != hipSuccess) return undo(e, "event");
+    (void)hipEventRecord(hs.ready, stream);
+    (void)hipEventRecord(stg.done, stream);
+    r->staging.push_back(stg);
     hs.live = true;
-    hipError_t e = hipMemcpy(r->d_scenes + slot, &hs.dev, sizeof(bps::SceneDev), hipMemcpyHostToDevice);
-    if (e != hipSuccess) { free_scene(hs); return fail(r, BPS_ERR_HIP, "bps_load_scene: scene table update: %s", hipGetErrorString(e)); }
     r->scenes[slot] = hs;
     r->plan_ids.clear();
     *out_handle = slot;
+    return BPS_OK;
+}
+
+}  // namespace
+
+bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
+                          const uint8_t* colors, bps_scene* out_handle) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    bps_status st = load_scene_on(r, vertices, V, indices, T, colors, r->load_stream, out_handle);
+    if (st != BPS_OK) return st;
+    BPS_HIP(r, hipStreamSynchronize(r->load_stream));
+    std::lock_guard<std::mutex> lock(r->mu);
+    HostScene& hs = r->scenes[*out_handle];
+    if (hs.ready) (void)hipEventDestroy(hs.ready);
+    hs.ready = nullptr;
+    return BPS_OK;
+}
+
+bps_status bps_load_scene_async(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
+                                const uint8_t* colors, void* copy_stream, bps_scene* out_handle) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    return load_scene_on(r, vertices, V, indices, T, colors, (hipStream_t)copy_stream, out_handle);
+}
+
+bps_status bps_scene_ready(bps_renderer* r, bps_scene scene, int32_t* ready) {
+    if (!r || !ready) return BPS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(r->mu);
+    if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
+        return fail(r, BPS_ERR_BAD_HANDLE, "bps_scene_ready: scene %d is not loaded", scene);
+    HostScene& hs = r->scenes[scene];
+    if (hs.ready && hipEventQuery(hs.ready) == hipSuccess) {
+        (void)hipEventDestroy(hs.ready);
+        hs.ready = nullptr;
+    }
+    (void)hipGetLastError();
+    *ready = hs.ready == nullptr ? 1 : 0;
     return BPS_OK;
 }
 
@@ -334,14 +497,25 @@ bps_status bps_pack_clusters(const float* vertices, uint32_t V, const uint32_t* 
 
 bps_status bps_unload_scene(bps_renderer* r, bps_scene scene) {
     if (!r) return BPS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(r->mu);
     if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
         return fail(r, BPS_ERR_BAD_HANDLE, "bps_unload_scene: scene %d is not loaded", scene);
     BPS_HIP(r, hipSetDevice(r->device));
-    BPS_HIP(r, hipDeviceSynchronize());
-    free_scene(r->scenes[scene]);
-    bps::SceneDev zero{};
-    BPS_HIP(r, hipMemcpy(r->d_scenes + scene, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    HostScene& hs = r->scenes[scene];
+    if (hs.ready) {   // the upload itself must be over before the block can be reused
+        BPS_HIP(r, hipEventSynchronize(hs.ready));
+        (void)hipEventDestroy(hs.ready);
+        hs.ready = nullptr;
+    }
+    // queued requests may still read the block and the table slot: park both until they are done
+    Retired x;
+    x.arena = hs.arena;
+    x.slot = scene;
+    x.last_use = hs.last_use;
+    r->retired.push_back(x);
+    hs = HostScene{};
     r->plan_ids.clear();
+    collect(r);
     return BPS_OK;
 }
 
@@ -349,6 +523,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
                       uint8_t* out_rgb, uint32_t* out_tri_id, void* stream_) {
     if (!r) return BPS_ERR_INVALID_ARG;
     if (B == 0) return BPS_OK;
+    std::lock_guard<std::mutex> lock(r->mu);
     if (!scene_ids || !view_proj || !out_depth) return fail(r, BPS_ERR_INVALID_ARG, "bps_render: null argument");
     if (B > (uint32_t)r->cfg.max_batch)
         return fail(r, BPS_ERR_INVALID_ARG, "bps_render: B=%u exceeds max_batch=%d", B, r->cfg.max_batch);
@@ -365,6 +540,21 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         min_clusters = std::min(min_clusters, r->scenes[s].dev.n_clusters);
     }
     BPS_HIP(r, hipSetDevice(r->device));
+    const uint64_t seq = ++r->seq;
+    for (uint32_t b = 0; b < B; ++b) {
+        HostScene& hs = r->scenes[scene_ids[b]];
+        if (hs.last_use == seq) continue;     // already handled for this request
+        hs.last_use = seq;
+        if (hs.ready) {                       // asynchronous upload: order this request after the copy
+            if (hipEventQuery(hs.ready) == hipSuccess) {
+                (void)hipEventDestroy(hs.ready);
+                hs.ready = nullptr;
+            } else {
+                (void)hipGetLastError();
+                BPS_HIP(r, hipStreamWaitEvent(stream, hs.ready, 0));
+            }
+        }
+    }
     const int H = r->cfg.height, W = r->cfg.width;
     const size_t HW = (size_t)H * W;
     const int S = plan_splits(r, B, min_clusters);
@@ -424,6 +614,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     if (slot.pending) {
         BPS_HIP(r, hipEventSynchronize(slot.done));
         slot.pending = false;
+        r->done_seq = std::max(r->done_seq, slot.seq);
     }
     if (slot.capacity < need) {
         if (slot.host) (void)hipHostFree(slot.host);
@@ -523,6 +714,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     if (ev_stop) BPS_HIP(r, hipEventRecord(ev_stop, stream));
     BPS_HIP(r, hipEventRecord(slot.done, stream));
     slot.pending = true;
+    slot.seq = seq;
     r->last_splits = (uint64_t)S;
     r->last_groups = (uint64_t)n_items;
     return BPS_OK;
@@ -590,6 +782,8 @@ bps_status bps_query(bps_renderer* r, bps_scene scene, int32_t what, uint64_t* v
     case 5: *value = r->last_groups; return BPS_OK;
     case 6: *value = (uint64_t)r->threads; return BPS_OK;
     case 7: *value = (uint64_t)r->lds; return BPS_OK;
+    case 8: *value = r->arena_allocs; return BPS_OK;
+    case 9: *value = (uint64_t)r->arena_pool.size() + (uint64_t)r->retired.size(); return BPS_OK;
     default: return fail(r, BPS_ERR_INVALID_ARG, "bps_query: unknown item %d", what);
     }
 }
