@@ -57,12 +57,15 @@ enum {
 typedef struct {
     int32_t device;          /* HIP device ordinal */
     int32_t max_batch;       /* largest B accepted by bps_render (>= 1) */
-    int32_t height, width;   /* frame size; multiples of 8, 8..128 */
+    int32_t height, width;   /* output frame size; multiples of 8, 8..128 */
     int32_t mode;            /* BPS_MODE_DEPTH or BPS_MODE_RGBD */
     float background_depth;  /* written where no triangle covers the pixel centre */
     int32_t splits;          /* work-groups per environment; 0 = choose from B and the device */
     int32_t threads;         /* work-group size: 0 = default, else 256, 384, 512 or 1024 */
     uint32_t flags;          /* BPS_FLAG_* bits, 0 = defaults */
+    int32_t supersample;     /* 0 or 1 = off; 2 = render at 2 height x 2 width and average 2x2 blocks into the
+                                output (depth: ((a+b)+(c+d))/4 in float32; colour: (a+b+c+d+2)>>2); then
+                                2 height and 2 width must be <= 128 and out_tri_id must be NULL */
 } bps_config;
 
 /* Create a renderer on cfg->device.  *out receives the handle.  Allocates the device scene

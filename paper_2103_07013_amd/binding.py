@@ -25,7 +25,7 @@ class BpsError(RuntimeError):
 class bps_config(ctypes.Structure):
     _fields_ = [("device", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("height", ctypes.c_int32),
                 ("width", ctypes.c_int32), ("mode", ctypes.c_int32), ("background_depth", ctypes.c_float),
-                ("splits", ctypes.c_int32), ("threads", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("splits", ctypes.c_int32), ("threads", ctypes.c_int32), ("flags", ctypes.c_uint32), ("supersample", ctypes.c_int32)]
 
 
 _lib = None
@@ -84,9 +84,9 @@ def _check(status, handle):
 
 
 def bps_create(device=0, max_batch=1024, height=64, width=64, mode=MODE_DEPTH, background_depth=0.0, splits=0,
-               threads=0, flags=0):
+               threads=0, flags=0, supersample=0):
     lib = load_library()
-    cfg = bps_config(device, max_batch, height, width, mode, background_depth, splits, threads, flags)
+    cfg = bps_config(device, max_batch, height, width, mode, background_depth, splits, threads, flags, supersample)
     h = ctypes.c_void_p()
     _check(lib.bps_create(ctypes.byref(cfg), ctypes.byref(h)), None)
     return h
@@ -229,9 +229,10 @@ class Renderer:
     """Convenience owner of one bps_renderer handle (same calls, object style)."""
 
     def __init__(self, max_batch, height=64, width=64, mode=MODE_DEPTH, device=0, background_depth=0.0, splits=0,
-                 threads=0, flags=0):
+                 threads=0, flags=0, supersample=0):
         self.H, self.W, self.mode, self.device = height, width, mode, device
-        self.handle = bps_create(device, max_batch, height, width, mode, background_depth, splits, threads, flags)
+        self.handle = bps_create(device, max_batch, height, width, mode, background_depth, splits, threads, flags,
+                                 supersample)
 
     def load_scene(self, vertices, indices, colors=None):
         return bps_load_scene(self.handle, vertices, indices, colors)

@@ -71,6 +71,9 @@ struct bps_renderer {
     int device = 0;
     int num_cu = 0;
     int threads = 512;
+    int ss = 1, rw = 64, rh = 64;     // supersampling factor and rendered frame size
+    float* ss_depth = nullptr;        // [max_batch][rh][rw] when supersampling
+    uint8_t* ss_rgb = nullptr;
     int tile_w = 64, tile_h = 64, tiles = 1;
     int list_cap = 2048;
     int round_target = 64;
@@ -179,8 +182,12 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
     if (!cfg || !out) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: null argument");
     *out = nullptr;
     if (cfg->max_batch < 1) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: max_batch must be >= 1");
-    if (cfg->height < 8 || cfg->height > 128 || cfg->height % 8 || cfg->width < 8 || cfg->width > 128 || cfg->width % 8)
-        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: height and width must be multiples of 8 in 8..128");
+    if (cfg->supersample != 0 && cfg->supersample != 1 && cfg->supersample != 2)
+        return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: supersample must be 0, 1 or 2");
+    const int ss = cfg->supersample == 2 ? 2 : 1;
+    if (cfg->height < 8 || cfg->height * ss > 128 || cfg->height % 8 || cfg->width < 8 || cfg->width * ss > 128 || cfg->width % 8)
+        return fail(nullptr, BPS_ERR_INVALID_ARG,
+                    "bps_create: height and width must be multiples of 8, at least 8 and at most 128 after supersampling");
     if (cfg->mode != BPS_MODE_DEPTH && cfg->mode != BPS_MODE_RGBD)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown mode %d", cfg->mode);
     if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 384 && cfg->threads != 512 && cfg->threads != 1024)
@@ -215,13 +222,16 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         // a work-group owns one tile of the frame: the whole frame up to 64 pixels per side,
         // otherwise the frame is cut into equal tiles of at most 64 pixels
         auto tile_of = [](int n) { int parts = (n + 63) / 64; return (n + parts - 1) / parts; };
-        r->tile_w = tile_of(cfg->width);
-        r->tile_h = tile_of(cfg->height);
+        r->ss = ss;
+        r->rw = cfg->width * ss;      // rendered size; the output is rw / ss by rh / ss
+        r->rh = cfg->height * ss;
+        r->tile_w = tile_of(r->rw);
+        r->tile_h = tile_of(r->rh);
         if (const char* e = std::getenv("BPS_TILE")) {   // tuning knob: force a tile size
             int v = std::atoi(e);
-            if (v >= 8 && v <= 128) { r->tile_w = std::min(v, cfg->width); r->tile_h = std::min(v, cfg->height); }
+            if (v >= 8 && v <= 128) { r->tile_w = std::min(v, r->rw); r->tile_h = std::min(v, r->rh); }
         }
-        r->tiles = ((cfg->width + r->tile_w - 1) / r->tile_w) * ((cfg->height + r->tile_h - 1) / r->tile_h);
+        r->tiles = ((r->rw + r->tile_w - 1) / r->tile_w) * ((r->rh + r->tile_h - 1) / r->tile_h);
         // preferred work-group size whose LDS footprint leaves room for a useful survivor list
         const int order[4] = {512, 384, 256, 1024};
         r->threads = 0;
@@ -241,7 +251,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         }
         if (!r->threads)
             return fail(r, BPS_ERR_UNSUPPORTED, "bps_create: a %dx%d frame needs %zu bytes of LDS, device offers %zu",
-                        cfg->height, cfg->width, bps::lds_bytes(r->tile_h, r->tile_w, cfg->threads ? cfg->threads : 256, 512),
+                        r->rh, r->rw, bps::lds_bytes(r->tile_h, r->tile_w, cfg->threads ? cfg->threads : 256, 512),
                         r->max_lds);
         r->list_cap = fit_cap(r->threads);
         r->round_target = r->list_cap / 2;
@@ -280,6 +290,8 @@ void bps_destroy(bps_renderer* r) {
     }
     if (r->gvis) (void)hipFree(r->gvis);
     if (r->ids) (void)hipFree(r->ids);
+    if (r->ss_depth) (void)hipFree(r->ss_depth);
+    if (r->ss_rgb) (void)hipFree(r->ss_rgb);
     if (r->d_stats) (void)hipFree(r->d_stats);
     if (r->d_scenes) (void)hipFree(r->d_scenes);
     for (hipEvent_t e : r->ev) (void)hipEventDestroy(e);
@@ -555,8 +567,17 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
             }
         }
     }
-    const int H = r->cfg.height, W = r->cfg.width;
+    const int H = r->rh, W = r->rw;       // rendered size
     const size_t HW = (size_t)H * W;
+    float* final_depth = out_depth;
+    uint8_t* final_rgb = out_rgb;
+    if (r->ss > 1) {
+        if (out_tri_id) return fail(r, BPS_ERR_INVALID_ARG, "bps_render: triangle ids are not available with supersampling");
+        if (!r->ss_depth) BPS_HIP(r, hipMalloc((void**)&r->ss_depth, (size_t)r->cfg.max_batch * HW * sizeof(float)));
+        if (rgbd && !r->ss_rgb) BPS_HIP(r, hipMalloc((void**)&r->ss_rgb, (size_t)r->cfg.max_batch * HW * 3));
+        out_depth = r->ss_depth;
+        out_rgb = r->ss_rgb;
+    }
     const int S = plan_splits(r, B, min_clusters);
 
     // ---- plan: one work item per (environment, slice of its scene's clusters); environments of
@@ -709,6 +730,10 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     }
     if (rgbd) {
         bps::launch_shade(stream, r->d_scenes, d_env_scene, d_vp, fp, B, out_tri_id, out_rgb);
+        BPS_HIP(r, hipGetLastError());
+    }
+    if (r->ss > 1) {
+        bps::launch_downsample(stream, out_depth, out_rgb, B, H, W, final_depth, final_rgb);
         BPS_HIP(r, hipGetLastError());
     }
     if (ev_stop) BPS_HIP(r, hipEventRecord(ev_stop, stream));

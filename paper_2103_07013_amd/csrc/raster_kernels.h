@@ -93,6 +93,8 @@ constexpr uint32_t kMaxPlannedItems = 16384;   // k_dispatch_order keeps one cos
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
                  const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch);
 hipError_t prepare_raster(int threads, size_t lds);
+void launch_downsample(hipStream_t stream, const float* depth, const uint8_t* rgb, uint32_t B, int H, int W,
+                       float* out_depth, uint8_t* out_rgb);
 void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
                   const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb);
 

@@ -148,6 +148,32 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
     out_rgb[3 * p + 2] = out[2];
 }
 
+// 2x2 box filter from the rendered frame to the output frame (the paper renders its 128-pixel
+// observations at twice the resolution and downsamples, Sec. 4.1).  Depth: ((a + b) + (c + d)) / 4
+// in float32 in that order; colour: (a + b + c + d + 2) >> 2 per channel.
+__global__ __launch_bounds__(256) void k_downsample(const float* __restrict__ depth, const uint8_t* __restrict__ rgb,
+                                                    uint32_t B, int H, int W, float* __restrict__ out_depth,
+                                                    uint8_t* __restrict__ out_rgb) {
+    const int oh = H >> 1, ow = W >> 1;
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= (size_t)B * oh * ow) return;
+    const int x = (int)(p % ow), y = (int)((p / ow) % oh);
+    const size_t b = p / ((size_t)ow * oh);
+    const size_t s = b * H * W + (size_t)(2 * y) * W + 2 * x;
+    out_depth[p] = ((depth[s] + depth[s + 1]) + (depth[s + W] + depth[s + W + 1])) * 0.25f;
+    if (rgb && out_rgb)
+        for (int c = 0; c < 3; ++c)
+            out_rgb[3 * p + c] = (uint8_t)(((int)rgb[3 * s + c] + (int)rgb[3 * (s + 1) + c] + (int)rgb[3 * (s + W) + c] +
+                                            (int)rgb[3 * (s + W + 1) + c] + 2) >> 2);
+}
+
+void launch_downsample(hipStream_t stream, const float* depth, const uint8_t* rgb, uint32_t B, int H, int W,
+                       float* out_depth, uint8_t* out_rgb) {
+    size_t n = (size_t)B * (H / 2) * (W / 2);
+    hipLaunchKernelGGL(k_downsample, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, depth, rgb, B, H, W, out_depth,
+                       out_rgb);
+}
+
 void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
                   const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb) {
     size_t n = (size_t)B * fp.H * fp.W;

@@ -31,7 +31,7 @@ def test_library_loads_and_exports_every_declared_symbol():
 def test_create_rejects_bad_configs_before_any_device_work():
     import paper_2103_07013_amd as bps
     for kw in (dict(max_batch=0), dict(height=60), dict(width=136), dict(height=4), dict(mode=7),
-               dict(threads=320), dict(splits=-1), dict(flags=64)):
+               dict(threads=320), dict(splits=-1), dict(flags=64), dict(supersample=3), dict(height=72, supersample=2)):
         with pytest.raises(bps.BpsError) as e:
             bps.bps_create(**kw)
         assert e.value.status == -1, kw
