@@ -150,6 +150,22 @@ def rotation_run(bps, torch, w, steps, warmup):
     return out
 
 
+def sweep(bps, torch, steps, warmup):
+    """Frames/s over batch size and resolution on the headline scenes (the shape of the paper's
+    stand-alone renderer figure, App. A.2).  Prints one JSON object per point."""
+    import synth
+    base = synth.build_config(3)
+    for res in (32, 64, 128):
+        for B in (1, 8, 64, 256, 512, 1024, 2048):
+            reps = (B + base.B - 1) // base.B
+            w = synth.Workload(3, base.scenes, np.tile(base.scene_ids, reps)[:B], np.tile(base.view_proj, (reps, 1, 1))[:B],
+                               res, res, False)
+            run = timed_run(bps, torch, w, 0, steps, warmup, 0, 0)
+            print(json.dumps({"sweep": True, "B": B, "H": res, "W": res, "frames_per_s": B * steps / run["dt"],
+                              "ms_per_request": run["dt"] * 1e3 / steps, "kernel_ms": run["kernel_ms_avg"],
+                              "work_groups": run["groups"], "splits": run["splits"]}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,6 +178,7 @@ def main():
     ap.add_argument("--no-cull", action="store_true", help="stream every cluster (no culling of clusters)")
     ap.add_argument("--no-occlusion", action="store_true", help="frustum culling of clusters only")
     ap.add_argument("--no-dispatch-order", action="store_true", help="launch work-groups in batch order")
+    ap.add_argument("--sweep", action="store_true", help="batch-size x resolution sweep instead of the single benchmark line")
     ap.add_argument("--rotate", action="store_true", help="also time rendering while scenes are being replaced")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed run: no diagnostics request, no full-stream run (for profiler runs)")
@@ -193,6 +210,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the renderer has no CPU path")
 
+    if args.sweep:
+        sweep(bps, torch, min(args.steps, 30), 5)
+        return
     w = synth.build_config(args.config, B=args.batch)
     flags = ((bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0) | (bps.FLAG_NO_OCCLUSION_CULL if args.no_occlusion else 0) |
              (bps.FLAG_NO_DISPATCH_ORDER if args.no_dispatch_order else 0))
