@@ -141,8 +141,9 @@ bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total
  *   out[16 g + 0] clusters whose bounds were tested      [1] clusters that passed the bounds tests
  *   [2] clusters that reached the triangle phase           [3] triangles sent to the clipper
  *   [4] clusters skipped because nearer geometry already covered their footprint
- *   [5] run time of the group's slowest wavefront, [15] of its first, in 100 MHz ticks
- *   [6..13] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
+ *   [5] run time of the group's slowest wavefront in 100 MHz ticks
+ *   [6] small triangles queued for per-lane rasterisation   [7] large triangles rasterised by a wavefront
+ *   [8..15] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
  *           in the set-up, bounds testing, barrier, depth sort, (unused), cluster processing,
  *           barrier and flush phases.
  * `capacity` is the room in `out` (in words), *written the number of words copied. */

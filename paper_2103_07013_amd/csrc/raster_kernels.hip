@@ -20,6 +20,7 @@ struct WaveLds {
     uint32_t* stage_oc; // [64] their outcodes
     uint32_t* smallq;   // [8][64] struct-of-arrays: xy0 xy1 xy2 iw0 iw1 iw2 id box
     uint32_t* clipq;    // [192] cluster << 7 | slot
+    uint32_t* tally;    // diagnostics: [0] small triangles queued, [1] large triangles rasterised (wave-private registers)
 };
 
 // One lane per queued small triangle: at most kSmallMax pixel centres each.
@@ -56,6 +57,7 @@ __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool wa
     u64 mask = ballot64(want);
     if (mask == 0) return;
     int n = __popcll(mask);
+    L.tally[0] += (uint32_t)n;
     int rank = (int)rank_below(mask);
     int room = 64 - count;
     int pos = count + rank;            // position if the queue were unbounded
@@ -139,8 +141,41 @@ __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool va
     bool small = valid && nx * ny <= kSmallMax;
     uint32_t box = (uint32_t)i_lo | ((uint32_t)j_lo << 8) | ((uint32_t)nx << 16) | ((uint32_t)ny << 24);
     push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, win, ctri_id);
-    u64 big = ballot64(valid && !small);
+    const bool medium = valid && !small && nx <= 8 && ny <= 8;
+    u64 med = ballot64(medium);
+    u64 big = ballot64(valid && !small && !medium);
+    L.tally[1] += (uint32_t)__popcll(med | big);
     const uint32_t id = (valid && !small) ? ctri_id[ref] : 0u;
+    // medium triangles (box within 8x8 pixels): four per pass, sixteen lanes each, 4x4 pixels per step
+    while (med) {
+        int src[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            src[k] = med ? __builtin_ctzll(med) : -1;
+            med &= med - 1;     // 0 & anything stays 0
+        }
+        const int g = lane >> 4;
+        const int from = g == 0 ? src[0] : g == 1 ? src[1] : g == 2 ? src[2] : src[3];
+        const bool on = from >= 0;
+        const int f = on ? from : 0;
+        const uint32_t mxy0 = (uint32_t)__shfl((int)xy0, f, 64), mxy1 = (uint32_t)__shfl((int)xy1, f, 64),
+                       mxy2 = (uint32_t)__shfl((int)xy2, f, 64);
+        const float miw0 = __shfl(iw0, f, 64), miw1 = __shfl(iw1, f, 64), miw2 = __shfl(iw2, f, 64);
+        const uint32_t mid = (uint32_t)__shfl((int)id, f, 64), mbox = (uint32_t)__shfl((int)box, f, 64);
+        const Setup st = make_setup(mxy0, mxy1, mxy2, miw0, miw1, miw2);
+        const int mi = (int)(mbox & 0xFFu), mj = (int)((mbox >> 8) & 0xFFu);
+        const int mnx = (int)((mbox >> 16) & 0xFFu), mny = (int)(mbox >> 24);
+        const int li = lane & 3, lj = (lane >> 2) & 3;
+#pragma unroll
+        for (int by = 0; by < 2; ++by)
+#pragma unroll
+            for (int bx = 0; bx < 2; ++bx) {
+                const int di = bx * 4 + li, dj = by * 4 + lj;
+                const bool act = on && di < mnx && dj < mny;
+                if (ballot64(act) == 0) continue;
+                shade_pixel(st, mi + di, mj + dj, act, mid, vis, win);
+            }
+    }
     while (big) {
         int src = __builtin_ctzll(big);
         big &= big - 1;
@@ -347,7 +382,9 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 
     u64* vis = reinterpret_cast<u64*>(smem);
     unsigned char* wbase = smem + (size_t)HW * 8 + (size_t)wave * kWaveLdsBytes;
+    uint32_t tally[2] = {0u, 0u};
     WaveLds L;
+    L.tally = tally;
     L.stage = reinterpret_cast<float2*>(wbase);
     L.stage_oc = reinterpret_cast<uint32_t*>(wbase + 64 * 8);
     L.smallq = reinterpret_cast<uint32_t*>(wbase + 64 * 12);
@@ -646,7 +683,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         uint32_t* rec = reinterpret_cast<uint32_t*>(list) + wave * 16;
         const uint32_t dt = (uint32_t)(wall_clock64() - t_start);
         rec[0] = st_tested; rec[1] = st_boxed; rec[2] = st_drawn; rec[3] = st_straddle; rec[4] = st_hidden; rec[5] = dt;
-        for (int k = 0; k < 8; ++k) rec[6 + k] = ticks[k];
+        rec[6] = tally[0]; rec[7] = tally[1];
+        for (int k = 0; k < 8; ++k) rec[8 + k] = ticks[k];
     }
     __syncthreads();
     if (stats && tid < 16) {
@@ -654,7 +692,6 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         unsigned long long sum = 0, mx = 0;
         for (int w = 0; w < NW; ++w) { sum += rec[w * 16 + tid]; mx = max(mx, (unsigned long long)rec[w * 16 + tid]); }
         stats[(size_t)blockIdx.x * 16 + tid] = tid == 5 ? mx : sum;      // word 5: longest wavefront of the group
-        if (tid == 15) stats[(size_t)blockIdx.x * 16 + 15] = rec[5];     // word 15: first wavefront
     }
 
     // ---- resolve this work-group's frame
