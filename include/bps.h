@@ -143,9 +143,10 @@ bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total
  *   [4] clusters skipped because nearer geometry already covered their footprint
  *   [5] run time of the group's slowest wavefront in 100 MHz ticks
  *   [6] small triangles queued for per-lane rasterisation   [7] large triangles rasterised by a wavefront
- *   [8..15] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
- *           in the set-up, bounds testing, barrier, depth sort, (unused), cluster processing,
- *           barrier and flush phases.
+ *   [8] clusters rejected against the coarse depth tiles before being queued
+ *   [9..15] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
+ *           in the bounds testing, barrier, depth sort, (unused), cluster processing, barrier
+ *           and flush phases.
  * `capacity` is the room in `out` (in words), *written the number of words copied. */
 bps_status bps_set_diagnostics(bps_renderer *r, int32_t enable);
 bps_status bps_read_diagnostics(bps_renderer *r, uint64_t *out, uint32_t capacity, uint32_t *written);

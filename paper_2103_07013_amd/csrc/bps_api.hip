@@ -76,7 +76,7 @@ struct bps_renderer {
     uint8_t* ss_rgb = nullptr;
     int tile_w = 64, tile_h = 64, tiles = 1;
     int list_cap = 2048;
-    int round_target = 64;
+    int round_target = 2048, first_round = 512;
     size_t lds = 0;
     size_t max_lds = 0;
     std::string error = "";
@@ -254,8 +254,9 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
                         r->rh, r->rw, bps::lds_bytes(r->tile_h, r->tile_w, cfg->threads ? cfg->threads : 256, 512),
                         r->max_lds);
         r->list_cap = fit_cap(r->threads);
-        r->round_target = r->list_cap / 2;
+        r->round_target = r->list_cap;
         if (const char* e = std::getenv("BPS_ROUND_TARGET")) r->round_target = std::max(1, std::atoi(e));   // tuning knob
+        if (const char* e = std::getenv("BPS_FIRST_ROUND")) r->first_round = std::max(1, std::atoi(e));     // tuning knob
         r->lds = bps::lds_bytes(r->tile_h, r->tile_w, r->threads, r->list_cap);
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
@@ -689,6 +690,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     fp.cull = (r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL) ? 0 : (r->cfg.flags & BPS_FLAG_NO_OCCLUSION_CULL) ? 1 : 2;
     fp.list_cap = r->list_cap;
     fp.round_target = r->round_target;
+    fp.first_round = r->first_round;
     fp.phase_timers = (r->want_stats && r->want_phase_timers) ? 1 : 0;
 
     unsigned long long* d_stats = nullptr;

@@ -50,6 +50,7 @@ struct FrameParams {
     int32_t cull;          // 0: stream every cluster; 1: frustum-cull clusters; 2: frustum + occlusion cull
     int32_t list_cap;      // capacity of the work-group's survivor list, in clusters
     int32_t round_target;  // survivors queued before a round's testing stops
+    int32_t first_round;   // the same for an environment's first round (kept short when occlusion culling is on)
     int32_t phase_timers;  // diagnostics: also time the kernel's phases (slows it down)
 };
 
@@ -64,13 +65,14 @@ constexpr uint32_t kNoProject = 0x80u; // outcode bit: vertex has no finite scre
 constexpr uint32_t kWaveLdsBytes = 64 * 12 + 8 * 64 * 4 + 192 * 4;
 
 constexpr int kOrderCap = 1024;        // blocks of one item that can be depth-sorted
+constexpr int kHizTiles = 64;          // 8x8-pixel tiles of a window of at most 64x64 pixels
 constexpr int kDepthBins = 128;        // bins of the per-round depth sort of surviving clusters
 
 // visibility buffer, per-wave blocks, survivor list (8 B record + two 2 B sort words per cluster),
 // block order, depth histogram and its prefix, four counters
 __host__ __device__ inline size_t lds_bytes(int tile_h, int tile_w, int threads, int list_cap) {
     return (size_t)tile_h * tile_w * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)list_cap * 12 + kOrderCap * 2 +
-           2 * kDepthBins * 4 + 32;
+           2 * kDepthBins * 4 + kHizTiles * 4 + 32;
 }
 
 template <int NT>

@@ -396,7 +396,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     uint16_t* perm = reinterpret_cast<uint16_t*>(shared + (size_t)fp.list_cap * 8 + kOrderCap * 2);   // [list_cap] pop order
     uint16_t* slot_in_bin = perm + fp.list_cap;                                                       // [list_cap]
     uint32_t* hist = reinterpret_cast<uint32_t*>(slot_in_bin + fp.list_cap);                          // [2][kDepthBins]
-    uint32_t* counters = hist + 2 * kDepthBins;
+    uint32_t* hiz = hist + 2 * kDepthBins;                                                            // [kHizTiles]
+    uint32_t* counters = hiz + kHizTiles;
     uint32_t* list_count = counters;       // survivors appended in this round
     uint32_t* pop_count = counters + 1;    // survivors handed out in this round
     uint32_t* next_block = counters + 2;   // blocks handed out so far (whole item)
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 
     int small_count = 0, clip_count = 0;
     // diagnostics (only when the host passes a counter block): per-wave tallies, one atomic each at the end
-    uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0, st_hidden = 0;
+    uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0, st_hidden = 0, st_hiz = 0;
     const unsigned long long t_start = stats ? wall_clock64() : 0ull;
     // phase timers (diagnostics only): ticks[k] accumulates the time since the previous TICK
     unsigned long long t_prev = t_start, t_c0 = 0;
@@ -447,6 +448,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 
     // ---- prologue: counters, and the item's blocks ordered near to far
     if (tid < 8) counters[tid] = 0u;
+    for (int t = tid; t < kHizTiles; t += NT) hiz[t] = 0xFFFFFFFFu;   // nothing drawn yet: no tile hides anything
     __syncthreads();
     const bool sorted = fp.cull != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)fp.list_cap && nb_item > 1;
     if (sorted) {
@@ -497,9 +499,13 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     //   phase B  wavefronts pop clusters from the list one at a time; a cluster whose footprint
     //            pixels all hold nearer depths by then is skipped (one lane per footprint pixel)
     TICK(0);
+    // the first round is kept short: what it draws (the nearest blocks) lets later rounds reject
+    // hidden clusters before they are queued
+    uint32_t round_target = occlusion ? min((uint32_t)fp.round_target, (uint32_t)fp.first_round) : (uint32_t)fp.round_target;
+    const int htx = (win.w + 7) >> 3;     // Hi-Z tiles per row of the window
     for (;;) {
         for (;;) {
-            if (*list_count >= (uint32_t)fp.round_target) break;
+            if (*list_count >= round_target) break;
             uint32_t r0 = 0, blk = 0;
             if (lane == 0) r0 = atomicAdd(reserved, 64u);
             r0 = __builtin_amdgcn_readfirstlane(r0);
@@ -527,6 +533,16 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 if (occlusion && visible) {
                     foot = box_footprint(M, fp, win, lx, ly, lz, hx, hy, hz, wb19);
                     visible = foot != kNoPixel;
+                    if (visible && (foot & 1u)) {
+                        // coarse test against the largest depth per 8x8 tile as of the end of the last round
+                        const int fx = (int)((foot >> 1) & 127u) - win.x0, fy = (int)((foot >> 8) & 127u) - win.y0;
+                        const int tx0 = fx >> 3, tx1 = (fx + (int)((foot >> 15) & 7u)) >> 3;
+                        const int ty0 = fy >> 3, ty1 = (fy + (int)((foot >> 18) & 7u)) >> 3;
+                        uint32_t zmax = max(max(hiz[ty0 * htx + tx0], hiz[ty0 * htx + tx1]),
+                                            max(hiz[ty1 * htx + tx0], hiz[ty1 * htx + tx1]));
+                        if ((wb19 << 12) > zmax) visible = false;
+                    }
+                    st_hiz += (uint32_t)__popcll(ballot64(!visible && foot != kNoPixel));
                 }
             }
             const u64 keep = ballot64(visible);
@@ -666,6 +682,19 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         TICK(5);
         __syncthreads();
         if (tid == 0) { *list_count = 0u; *pop_count = 0u; *reserved = 0u; }
+        if (occlusion && *next_block < nb_visit) {
+            // Hi-Z: largest stored depth word per 8x8-pixel tile of the window (empty pixels read as
+            // 0xFFFFFFFF); one wavefront per tile, butterfly maximum
+            const int hty = (win.h + 7) >> 3;
+            for (int t = wave; t < htx * hty; t += NW) {
+                const int px = ((t % htx) << 3) + (lane & 7), py = ((t / htx) << 3) + (lane >> 3);
+                uint32_t dbits = (px < win.w && py < win.h) ? vis_hi[2 * (py * win.w + px)] : 0u;
+#pragma unroll
+                for (int sh = 32; sh >= 1; sh >>= 1) dbits = max(dbits, (uint32_t)__shfl_xor((int)dbits, sh, 64));
+                if (lane == 0) hiz[t] = dbits;
+            }
+        }
+        round_target = (uint32_t)fp.round_target;
         __syncthreads();
         TICK(6);
     }
@@ -683,8 +712,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         uint32_t* rec = reinterpret_cast<uint32_t*>(list) + wave * 16;
         const uint32_t dt = (uint32_t)(wall_clock64() - t_start);
         rec[0] = st_tested; rec[1] = st_boxed; rec[2] = st_drawn; rec[3] = st_straddle; rec[4] = st_hidden; rec[5] = dt;
-        rec[6] = tally[0]; rec[7] = tally[1];
-        for (int k = 0; k < 8; ++k) rec[8 + k] = ticks[k];
+        rec[6] = tally[0]; rec[7] = tally[1]; rec[8] = st_hiz;
+        for (int k = 1; k < 8; ++k) rec[8 + k] = ticks[k];
     }
     __syncthreads();
     if (stats && tid < 16) {
