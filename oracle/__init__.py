@@ -38,6 +38,12 @@ def _load():
         lib.oracle_render.restype = ctypes.c_int
         lib.oracle_render.argtypes = [f32p, ctypes.c_uint32, u32p, ctypes.c_uint32, u8p, f32p, ctypes.c_uint32,
                                       ctypes.c_int, ctypes.c_int, ctypes.c_float, f32p, u32p, u8p, u32p, ctypes.c_int]
+        lib.oracle_render_textured.restype = ctypes.c_int
+        lib.oracle_render_textured.argtypes = [f32p, ctypes.c_uint32, u32p, ctypes.c_uint32, u8p, f32p, u8p, ctypes.c_int,
+                                               ctypes.c_int, f32p, ctypes.c_uint32, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_float, f32p, u32p, u8p, u32p, ctypes.c_int]
+        lib.oracle_sample.restype = None
+        lib.oracle_sample.argtypes = [u8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_float, u8p]
         lib.oracle_cover_fixed.restype = None
         lib.oracle_cover_fixed.argtypes = [i32p, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, u32p]
         lib.oracle_clip.restype = ctypes.c_int
@@ -50,8 +56,10 @@ def _p(a, t):
     return None if a is None else a.ctypes.data_as(ctypes.POINTER(t))
 
 
-def render_scene(vertices, indices, view_proj, H, W, colors=None, background=0.0, want_cover=False, nthreads=0):
-    """Render every matrix in view_proj[B,4,4] against one mesh.
+def render_scene(vertices, indices, view_proj, H, W, colors=None, background=0.0, want_cover=False, nthreads=0,
+                 uvs=None, texture=None):
+    """Render every matrix in view_proj[B,4,4] against one mesh.  With uvs [V,2] and texture
+    [th,tw,3] uint8 the colour output is sampled from the texture (rule N10).
 
     Returns dict(depth f32 [B,H,W], tri_id u32 [B,H,W], rgb u8 [B,H,W,3] | None,
     cover u32 [B,H,W] | None, threads int)."""
@@ -63,19 +71,27 @@ def render_scene(vertices, indices, view_proj, H, W, colors=None, background=0.0
         raise ValueError("index out of range")
     B = m.shape[0]
     c = None if colors is None else np.ascontiguousarray(colors, np.uint8).reshape(-1, 3)
+    uv = None if uvs is None else np.ascontiguousarray(uvs, np.float32).reshape(-1, 2)
+    tex = None if texture is None else np.ascontiguousarray(texture, np.uint8)
+    if (uv is None) != (tex is None):
+        raise ValueError("uvs and texture go together")
     depth = np.empty((B, H, W), np.float32)
     tid = np.empty((B, H, W), np.uint32)
-    rgb = np.zeros((B, H, W, 3), np.uint8) if c is not None else None
+    rgb = np.zeros((B, H, W, 3), np.uint8) if (c is not None or tex is not None) else None
     cover = np.zeros((B, H, W), np.uint32) if want_cover else None
-    used = lib.oracle_render(_p(v, ctypes.c_float), v.shape[0], _p(i, ctypes.c_uint32), i.shape[0],
-                             _p(c, ctypes.c_uint8), _p(m, ctypes.c_float), B, H, W, float(background),
-                             _p(depth, ctypes.c_float), _p(tid, ctypes.c_uint32), _p(rgb, ctypes.c_uint8),
-                             _p(cover, ctypes.c_uint32), int(nthreads))
+    used = lib.oracle_render_textured(_p(v, ctypes.c_float), v.shape[0], _p(i, ctypes.c_uint32), i.shape[0],
+                                      _p(c, ctypes.c_uint8), _p(uv, ctypes.c_float), _p(tex, ctypes.c_uint8),
+                                      0 if tex is None else tex.shape[1], 0 if tex is None else tex.shape[0],
+                                      _p(m, ctypes.c_float), B, H, W, float(background),
+                                      _p(depth, ctypes.c_float), _p(tid, ctypes.c_uint32), _p(rgb, ctypes.c_uint8),
+                                      _p(cover, ctypes.c_uint32), int(nthreads))
     return dict(depth=depth, tri_id=tid, rgb=rgb, cover=cover, threads=used)
 
 
-def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0, nthreads=0, want_cover=False):
-    """Render a mixed batch: env b uses scenes[scene_ids[b]] (objects with .vertices/.indices/.colors)."""
+def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0, nthreads=0, want_cover=False,
+                 textured=False):
+    """Render a mixed batch: env b uses scenes[scene_ids[b]] (objects with .vertices/.indices/.colors,
+    and .uvs/.texture when textured)."""
     scene_ids = np.asarray(scene_ids)
     B = scene_ids.shape[0]
     depth = np.empty((B, H, W), np.float32)
@@ -86,8 +102,9 @@ def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0,
     for k in np.unique(scene_ids):
         sel = np.nonzero(scene_ids == k)[0]
         s = scenes[int(k)]
-        r = render_scene(s.vertices, s.indices, view_proj[sel], H, W, colors=s.colors if rgbd else None,
-                         background=background, nthreads=nthreads, want_cover=want_cover)
+        r = render_scene(s.vertices, s.indices, view_proj[sel], H, W, colors=s.colors if (rgbd and not textured) else None,
+                         background=background, nthreads=nthreads, want_cover=want_cover,
+                         uvs=s.uvs if textured else None, texture=s.texture if textured else None)
         depth[sel], tid[sel] = r["depth"], r["tri_id"]
         if rgbd:
             rgb[sel] = r["rgb"]
@@ -95,6 +112,15 @@ def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0,
             cover[sel] = r["cover"]
         threads = r["threads"]
     return dict(depth=depth, tri_id=tid, rgb=rgb, cover=cover, threads=threads)
+
+
+def sample(texture, level, u, v):
+    """The RGB texel rule N10 picks for (u, v) at mip level `level`."""
+    lib = _load()
+    tex = np.ascontiguousarray(texture, np.uint8)
+    out = np.zeros(3, np.uint8)
+    lib.oracle_sample(_p(tex, ctypes.c_uint8), tex.shape[1], tex.shape[0], int(level), float(u), float(v), _p(out, ctypes.c_uint8))
+    return out
 
 
 def cover_fixed(xy, H, W):

@@ -33,6 +33,14 @@
  *       the pixel keeps the minimum key.
  *   N8  uncovered pixel: depth = background, id = 0xFFFFFFFF, rgb = 0.
  *   N9  colour: cn = fma(e2*iw2,c2, fma(e1*iw1,c1, (e0*iw0)*c0)); out = clamp(lrint(cn/num)).
+ *   N10 texture (stand-in for the paper's textured RGB sensor, Sec. 4.1): per-vertex (u,v) are
+ *       interpolated like colours, u = un/num.  Texture w x h (powers of two), RGB8, with a mip
+ *       pyramid: each level halves both sides (not below 1) and a texel is (a+b+c+d+2)>>2 of its
+ *       2x2 parents (parents clamped at the border).  One level per fan triangle, from the
+ *       oriented vertices: auv = |fma(du1,dv2, -(du2*dv1))|, r = auv*w*h*65536 / A2 (texels per
+ *       pixel), level = number of times r can be quartered while r >= 4 (at most the last level).
+ *       Sample: fu = u - floor(u) (0 if that is not in [0,1)), x = min((int)(fu*lw), lw-1), likewise y;
+ *       the pixel takes that texel, no filtering.
  *
  * Everything after N4 is exact integer arithmetic in int64.
  */
@@ -52,10 +60,16 @@ typedef struct {
 } overt;
 
 typedef struct {
+    int w, h, levels;
+    uint8_t **level; /* level[l] = RGB8 texels of size max(w>>l,1) x max(h>>l,1) */
+} otexture;
+
+typedef struct {
     int H, W;
     uint64_t *key;   /* [H*W] */
     uint32_t *cover; /* [H*W] or NULL: number of covering sub-triangles */
     uint8_t *rgb;    /* [H*W*3] or NULL */
+    const otexture *tex; /* when set, attribute slots 0,1 hold (u,v) and colour comes from the texture */
 } oframe;
 
 static float plane_dist(const overt *v, int k)
@@ -192,7 +206,34 @@ static void raster_subtri(oframe *f, const int64_t Xi[3], const int64_t Yi[3], c
             uint64_t k = ((uint64_t)dbits << 32) | (uint64_t)id;
             if (k < f->key[p]) {
                 f->key[p] = k;
-                if (f->rgb) {
+                if (f->rgb && f->tex) {
+                    const otexture *tx = f->tex;
+                    /* one mip level per fan triangle, from its oriented vertices */
+                    float du1 = col[1][0] - col[0][0], dv1 = col[1][1] - col[0][1];
+                    float du2 = col[2][0] - col[0][0], dv2 = col[2][1] - col[0][1];
+                    float auv = fabsf(fmaf(du1, dv2, -(du2 * dv1)));
+                    float r = ((auv * (float)tx->w) * (float)tx->h) * 65536.0f / (float)A2;
+                    int L = 0;
+                    while (L < tx->levels - 1 && r >= 4.0f) { r *= 0.25f; ++L; }
+                    int lw = tx->w >> L, lh = tx->h >> L;
+                    if (lw < 1) lw = 1;
+                    if (lh < 1) lh = 1;
+                    float uv[2];
+                    for (int c = 0; c < 2; ++c) {
+                        float cn = fmaf(e2 * iw[2], col[2][c], fmaf(e1 * iw[1], col[1][c], (e0 * iw[0]) * col[0][c]));
+                        float v = cn / num;
+                        float fr = v - floorf(v);
+                        if (!(fr >= 0.0f && fr < 1.0f)) fr = 0.0f;
+                        uv[c] = fr;
+                    }
+                    int x = (int)(uv[0] * (float)lw), y = (int)(uv[1] * (float)lh);
+                    if (x > lw - 1) x = lw - 1;
+                    if (y > lh - 1) y = lh - 1;
+                    const uint8_t *t = tx->level[L] + 3 * ((size_t)y * (size_t)lw + (size_t)x);
+                    f->rgb[p * 3 + 0] = t[0];
+                    f->rgb[p * 3 + 1] = t[1];
+                    f->rgb[p * 3 + 2] = t[2];
+                } else if (f->rgb) {
                     for (int c = 0; c < 3; ++c) {
                         float cn = fmaf(e2 * iw[2], col[2][c], fmaf(e1 * iw[1], col[1][c], (e0 * iw[0]) * col[0][c]));
                         float v = cn / num;
@@ -237,7 +278,7 @@ static void raster_clip_tri(oframe *f, const overt tri[3], uint32_t id)
 }
 
 static void render_env(oframe *f, const float *verts, const uint32_t *idx, uint32_t T, const uint8_t *colors,
-                       const float *M)
+                       const float *uvs, const float *M)
 {
     for (uint32_t t = 0; t < T; ++t) {
         overt tri[3];
@@ -245,6 +286,11 @@ static void render_env(oframe *f, const float *verts, const uint32_t *idx, uint3
             uint32_t vi = idx[3 * (size_t)t + v];
             transform(M, verts + 3 * (size_t)vi, &tri[v]);
             for (int c = 0; c < 3; ++c) tri[v].col[c] = colors ? (float)colors[3 * (size_t)vi + c] : 0.0f;
+            if (uvs) {
+                tri[v].col[0] = uvs[2 * (size_t)vi + 0];
+                tri[v].col[1] = uvs[2 * (size_t)vi + 1];
+                tri[v].col[2] = 0.0f;
+            }
         }
         raster_clip_tri(f, tri, t);
     }
@@ -256,11 +302,71 @@ static void render_env(oframe *f, const float *verts, const uint32_t *idx, uint3
  * depth [B][H][W] float, tri_id [B][H][W] uint32 (may be NULL), rgb [B][H][W][3] uint8
  * (NULL unless colors given), cover [B][H][W] uint32 (may be NULL).
  * nthreads <= 0 uses every core.  Returns the number of threads used. */
+/* N10: build the mip pyramid of an RGB8 texture (w, h powers of two). */
+static otexture *build_pyramid(const uint8_t *texels, int w, int h)
+{
+    otexture *t = (otexture *)malloc(sizeof(otexture));
+    t->w = w;
+    t->h = h;
+    int levels = 1;
+    for (int a = w, b = h; a > 1 || b > 1; a = a > 1 ? a / 2 : 1, b = b > 1 ? b / 2 : 1) ++levels;
+    t->levels = levels;
+    t->level = (uint8_t **)malloc((size_t)levels * sizeof(uint8_t *));
+    t->level[0] = (uint8_t *)malloc((size_t)w * h * 3);
+    memcpy(t->level[0], texels, (size_t)w * h * 3);
+    int pw = w, ph = h;
+    for (int l = 1; l < levels; ++l) {
+        int lw = pw > 1 ? pw / 2 : 1, lh = ph > 1 ? ph / 2 : 1;
+        t->level[l] = (uint8_t *)malloc((size_t)lw * lh * 3);
+        for (int y = 0; y < lh; ++y)
+            for (int x = 0; x < lw; ++x) {
+                int x0 = 2 * x, y0 = 2 * y, x1 = 2 * x + 1, y1 = 2 * y + 1;
+                if (x0 > pw - 1) x0 = pw - 1;
+                if (x1 > pw - 1) x1 = pw - 1;
+                if (y0 > ph - 1) y0 = ph - 1;
+                if (y1 > ph - 1) y1 = ph - 1;
+                for (int c = 0; c < 3; ++c) {
+                    int s = t->level[l - 1][3 * (y0 * pw + x0) + c] + t->level[l - 1][3 * (y0 * pw + x1) + c] +
+                            t->level[l - 1][3 * (y1 * pw + x0) + c] + t->level[l - 1][3 * (y1 * pw + x1) + c];
+                    t->level[l][3 * (y * lw + x) + c] = (uint8_t)((s + 2) >> 2);
+                }
+            }
+        pw = lw;
+        ph = lh;
+    }
+    return t;
+}
+
+static void free_pyramid(otexture *t)
+{
+    if (!t) return;
+    for (int l = 0; l < t->levels; ++l) free(t->level[l]);
+    free(t->level);
+    free(t);
+}
+
+int oracle_render_textured(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
+                           const float *uvs, const uint8_t *texels, int tex_w, int tex_h, const float *view_proj,
+                           uint32_t B, int H, int W, float background, float *depth, uint32_t *tri_id, uint8_t *rgb,
+                           uint32_t *cover, int nthreads);
+
 int oracle_render(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
                   const float *view_proj, uint32_t B, int H, int W, float background, float *depth,
                   uint32_t *tri_id, uint8_t *rgb, uint32_t *cover, int nthreads)
 {
+    return oracle_render_textured(verts, V, idx, T, colors, NULL, NULL, 0, 0, view_proj, B, H, W, background, depth, tri_id,
+                                  rgb, cover, nthreads);
+}
+
+/* As oracle_render, with optional texturing: uvs [V][2] float and texels [tex_h][tex_w][3] uint8
+ * (both NULL for per-vertex colours). */
+int oracle_render_textured(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
+                           const float *uvs, const uint8_t *texels, int tex_w, int tex_h, const float *view_proj,
+                           uint32_t B, int H, int W, float background, float *depth, uint32_t *tri_id, uint8_t *rgb,
+                           uint32_t *cover, int nthreads)
+{
     (void)V;
+    otexture *tex = (uvs && texels) ? build_pyramid(texels, tex_w, tex_h) : NULL;
     int used = 1;
 #ifdef _OPENMP
     if (nthreads <= 0) nthreads = omp_get_num_procs();
@@ -278,9 +384,10 @@ int oracle_render(const float *verts, uint32_t V, const uint32_t *idx, uint32_t 
         for (size_t p = 0; p < npix; ++p) f.key[p] = ~(uint64_t)0;
         f.cover = cover ? cover + (size_t)b * npix : NULL;
         if (f.cover) memset(f.cover, 0, npix * sizeof(uint32_t));
-        f.rgb = (rgb && colors) ? rgb + (size_t)b * npix * 3 : NULL;
+        f.rgb = (rgb && (colors || tex)) ? rgb + (size_t)b * npix * 3 : NULL;
+        f.tex = tex;
         if (f.rgb) memset(f.rgb, 0, npix * 3);
-        render_env(&f, verts, idx, T, colors, view_proj + 16 * (size_t)b);
+        render_env(&f, verts, idx, T, colors, tex ? uvs : NULL, view_proj + 16 * (size_t)b);
         for (size_t p = 0; p < npix; ++p) {
             uint64_t k = f.key[p];
             float d = background;
@@ -295,7 +402,26 @@ int oracle_render(const float *verts, uint32_t V, const uint32_t *idx, uint32_t 
         }
         free(f.key);
     }
+    free_pyramid(tex);
     return used;
+}
+
+/* N10 alone: the texel the sampling rule picks for (u, v) at mip level L. */
+void oracle_sample(const uint8_t *texels, int tex_w, int tex_h, int L, float u, float v, uint8_t *rgb_out)
+{
+    otexture *tx = build_pyramid(texels, tex_w, tex_h);
+    if (L > tx->levels - 1) L = tx->levels - 1;
+    int lw = tx->w >> L, lh = tx->h >> L;
+    if (lw < 1) lw = 1;
+    if (lh < 1) lh = 1;
+    float fu = u - floorf(u), fv = v - floorf(v);
+    if (!(fu >= 0.0f && fu < 1.0f)) fu = 0.0f;
+    if (!(fv >= 0.0f && fv < 1.0f)) fv = 0.0f;
+    int x = (int)(fu * (float)lw), y = (int)(fv * (float)lh);
+    if (x > lw - 1) x = lw - 1;
+    if (y > lh - 1) y = lh - 1;
+    memcpy(rgb_out, tx->level[L] + 3 * ((size_t)y * lw + x), 3);
+    free_pyramid(tx);
 }
 
 /* N5-N6 alone: coverage counts of triangles given directly in 1/256-pixel integer
@@ -305,7 +431,7 @@ void oracle_cover_fixed(const int32_t *xy, uint32_t n, int H, int W, uint32_t *c
     size_t npix = (size_t)H * (size_t)W;
     uint64_t *key = (uint64_t *)malloc(npix * sizeof(uint64_t));
     for (size_t p = 0; p < npix; ++p) key[p] = ~(uint64_t)0;
-    oframe f = {H, W, key, cover, NULL};
+    oframe f = {H, W, key, cover, NULL, NULL};
     for (uint32_t t = 0; t < n; ++t) {
         int64_t X[3], Y[3];
         float iw[3] = {1.0f, 1.0f, 1.0f};

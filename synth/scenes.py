@@ -22,6 +22,8 @@ class Scene:
     vertices: np.ndarray            # float32 [V,3]
     indices: np.ndarray             # uint32  [T,3]
     colors: np.ndarray              # uint8   [V,3]
+    uvs: np.ndarray                 # float32 [V,2] texture coordinates (one repeat per metre of surface)
+    texture: np.ndarray             # uint8   [256,256,3] procedural texture of the scene
     extent: tuple                   # (x_size, z_size) of the floor rectangle, origin at (0,0)
     boxes: np.ndarray = field(default_factory=lambda: np.zeros((0, 4)))      # footprints x0,z0,x1,z1
     cylinders: np.ndarray = field(default_factory=lambda: np.zeros((0, 3)))  # cx,cz,r
@@ -44,7 +46,7 @@ class _MeshBuilder:
 
     def __init__(self, count_only: bool):
         self.count_only = count_only
-        self.verts, self.tris, self.obj = [], [], []
+        self.verts, self.tris, self.obj, self.uv = [], [], [], []
         self.nv = 0
         self.nt = 0
         self.cur_obj = 0
@@ -79,6 +81,8 @@ class _MeshBuilder:
         self.verts.append(P.reshape(-1, 3))
         self.tris.append(tri.reshape(-1, 3))
         self.obj.append(np.full(P.shape[0] * P.shape[1], self.cur_obj, np.int64))
+        lu, lv = float(np.linalg.norm(du)), float(np.linalg.norm(dv))
+        self.uv.append(np.stack([S * lu, Tt * lv], -1).reshape(-1, 2))
         self.nv += P.shape[0] * P.shape[1]
 
     def disc(self, centre, r, nseg, nring):
@@ -105,10 +109,12 @@ class _MeshBuilder:
         self.verts.append(P)
         self.tris.append(np.concatenate(tris, 0))
         self.obj.append(np.full(P.shape[0], self.cur_obj, np.int64))
+        self.uv.append(P[:, [0, 2]].copy())
         self.nv += P.shape[0]
 
     def finish(self):
-        return (np.concatenate(self.verts, 0), np.concatenate(self.tris, 0), np.concatenate(self.obj, 0))
+        return (np.concatenate(self.verts, 0), np.concatenate(self.tris, 0), np.concatenate(self.obj, 0),
+                np.concatenate(self.uv, 0))
 
 
 def _n(length, cell):
@@ -165,6 +171,7 @@ def _add_cylinder(mb, cx, cz, r, h, segs, cell):
         mb.verts.append(P)
         mb.tris.append(tri)
         mb.obj.append(np.full(P.shape[0], mb.cur_obj, np.int64))
+        mb.uv.append(np.stack([A * r, Y], -1).reshape(-1, 2))
         mb.nv += P.shape[0]
     mb.disc((cx, h, cz), r, nseg, nring)
 
@@ -198,6 +205,14 @@ def _colorize(rng, obj_ids, nobj):
     return np.clip(base[obj_ids] + noise, 0, 255).astype(np.uint8)
 
 
+def _texture(rng, size=256):
+    """Coloured checker (8 x 8 cells) with per-texel noise: structure at every mip level."""
+    cells = rng.integers(40, 216, size=(8, 8, 3))
+    tex = np.repeat(np.repeat(cells, size // 8, 0), size // 8, 1)
+    tex = tex + rng.integers(-24, 25, size=(size, size, 3))
+    return np.clip(tex, 0, 255).astype(np.uint8)
+
+
 def make_room_scene(target_T=10_000, seed=1000, n_boxes=20):
     """Single 10 x 8 x 3 m room with axis-aligned box furniture standing on the floor."""
     rng = np.random.default_rng(seed)
@@ -218,10 +233,10 @@ def make_room_scene(target_T=10_000, seed=1000, n_boxes=20):
     cell = _search_cell(build, target_T)
     mb = _MeshBuilder(count_only=False)
     build(mb, cell)
-    P, Tt, obj = mb.finish()
+    P, Tt, obj, uv = mb.finish()
     colors = _colorize(rng, obj, mb.cur_obj)
     fp = np.array([[b[0], b[1], b[0] + b[2], b[1] + b[3]] for b in boxes])
-    return Scene(P.astype(np.float32), Tt.astype(np.uint32), colors, (ROOM_X, ROOM_Z),
+    return Scene(P.astype(np.float32), Tt.astype(np.uint32), colors, uv.astype(np.float32), _texture(rng), (ROOM_X, ROOM_Z),
                  boxes=fp, cell=cell, seed=seed)
 
 
@@ -278,10 +293,11 @@ def make_multiroom_scene(target_T=200_000, seed=1000, n_objects=150, rooms=(3, 2
     cell = _search_cell(build, target_T)
     mb = _MeshBuilder(count_only=False)
     build(mb, cell)
-    P, Tt, obj = mb.finish()
+    P, Tt, obj, uv = mb.finish()
     colors = _colorize(rng, obj, mb.cur_obj)
     fp = np.array([[o[1], o[2], o[1] + o[3], o[2] + o[4]] for o in objs if o[0] == "box"]).reshape(-1, 4)
     cy = np.array([[o[1], o[2], o[3]] for o in objs if o[0] == "cyl"]).reshape(-1, 3)
-    return Scene(P.astype(np.float32), Tt.astype(np.uint32), colors, (SX, SZ), boxes=fp, cylinders=cy,
+    return Scene(P.astype(np.float32), Tt.astype(np.uint32), colors, uv.astype(np.float32), _texture(rng), (SX, SZ),
+                 boxes=fp, cylinders=cy,
                  wall_x=tuple(i * ROOM_X for i in range(1, RX)),
                  wall_z=tuple(j * ROOM_Z for j in range(1, RZ)), cell=cell, seed=seed)

@@ -95,7 +95,8 @@ def test_random_soup_with_heavy_clipping():
     c = np.stack([rng.uniform(-4, 4, n), rng.uniform(-4, 4, n), rng.uniform(-9, 2, n)], 1)
     v = (c[:, None, :] + rng.uniform(-1.5, 1.5, (n, 3, 3))).reshape(-1, 3).astype(np.float32)
     idx = np.arange(3 * n, dtype=np.uint32).reshape(n, 3)
-    scene = synth.Scene(v, idx, np.zeros((3 * n, 3), np.uint8), (1, 1))
+    scene = synth.Scene(v, idx, np.zeros((3 * n, 3), np.uint8), np.zeros((3 * n, 2), np.float32),
+                        np.zeros((4, 4, 3), np.uint8), (1, 1))
     Ms = np.stack([synth.view_proj_from_pose((0.1 * k, -0.2, 0.5), 0.4 * k, 0.15 * (k - 3), near=0.05, far=12.0)
                    for k in range(8)])
     for (H, W) in ((64, 64), (32, 96), (128, 128)):

@@ -569,3 +569,115 @@ def _on_segment(g, M, P, Q):
     if not (1e-4 < t < 1 - 1e-4):
         return False
     return np.linalg.norm(p + t * d - g) <= 1e-4 * (1 + np.linalg.norm(g))
+
+
+# ---------------------------------------------------------------- 7. textures (rule N10)
+
+def _pyramid_reference(tex):
+    """Independent numpy construction of the mip pyramid: (a+b+c+d+2)>>2 over 2x2 parents."""
+    levels = [tex.astype(np.int32)]
+    while levels[-1].shape[0] > 1 or levels[-1].shape[1] > 1:
+        t = levels[-1]
+        h, w = t.shape[:2]
+        ys = np.minimum(np.arange(max(h // 2, 1))[:, None] * 2 + np.array([0, 1])[None, :], h - 1)
+        xs = np.minimum(np.arange(max(w // 2, 1))[:, None] * 2 + np.array([0, 1])[None, :], w - 1)
+        s = (t[ys[:, 0]][:, xs[:, 0]] + t[ys[:, 0]][:, xs[:, 1]] + t[ys[:, 1]][:, xs[:, 0]] + t[ys[:, 1]][:, xs[:, 1]])
+        levels.append((s + 2) >> 2)
+    return [l.astype(np.uint8) for l in levels]
+
+
+def _corner_quad(d, W, H):
+    """Camera-facing quad at distance d exactly filling the frame (corners on the frame corners)."""
+    return np.array([[-d, d, -d], [d, d, -d], [d, -d, -d], [-d, -d, -d]], np.float32)
+
+
+def test_texture_sampling_rule_on_single_lookups():
+    rng = np.random.default_rng(4)
+    tex = rng.integers(0, 256, (8, 16, 3)).astype(np.uint8)          # h = 8, w = 16
+    pyr = _pyramid_reference(tex)
+    assert [p.shape[:2] for p in pyr] == [(8, 16), (4, 8), (2, 4), (1, 2), (1, 1)]
+    for L, lv in enumerate(pyr):
+        lh, lw = lv.shape[:2]
+        for (u, v) in [(0.0, 0.0), (0.5, 0.5), (0.999999, 0.999999), (1.0, 1.0), (-0.25, 2.75), (3.0625, -1.9375)]:
+            fu, fv = u - math.floor(u), v - math.floor(v)
+            x, y = min(int(np.float32(fu) * lw), lw - 1), min(int(np.float32(fv) * lh), lh - 1)
+            assert np.array_equal(oracle.sample(tex, L, u, v), lv[y, x]), (L, u, v)
+    assert np.array_equal(oracle.sample(tex, 0, float("nan"), float("inf")), tex[0, 0])
+    assert np.array_equal(oracle.sample(tex, 99, 0.7, 0.2), pyr[-1][0, 0])    # level clamps to the last one
+    assert np.array_equal(oracle.sample(tex, 0, -1e-9, 0.0), tex[0, 0])       # frac rounds to 1.0: guarded
+
+
+@pytest.mark.parametrize("scale,level", [(1, 0), (2, 1), (4, 2), (8, 3)])
+def test_textured_quad_picks_the_expected_mip_level_and_texel(scale, level):
+    """Frame-filling quad, uv 0..1, texture `scale` times the frame size: every pixel covers
+    scale x scale texels, so the level is log2(scale) and pixel (i, j) shows that level's texel (i, j)."""
+    H = W = 32
+    rng = np.random.default_rng(9)
+    tex = rng.integers(0, 256, (H * scale, W * scale, 3)).astype(np.uint8)
+    v = _corner_quad(2.0, W, H)
+    uv = np.array([[0, 0], [1, 0], [1, 1], [0, 1]], np.float32)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    r = oracle.render_scene(v, idx, cam()[None], H, W, uvs=uv, texture=tex)
+    assert (r["tri_id"][0] != NOHIT).all()
+    assert np.array_equal(r["rgb"][0], _pyramid_reference(tex)[level])
+
+
+def test_texture_wraps_and_constant_texture_gives_constant_colour():
+    H = W = 16
+    v = _corner_quad(2.0, W, H)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    tex = np.random.default_rng(1).integers(0, 256, (8, 8, 3)).astype(np.uint8)
+    uv = np.array([[0, 0], [2, 0], [2, 2], [0, 2]], np.float32)          # two repeats across the frame
+    r = oracle.render_scene(v, idx, cam()[None], H, W, uvs=uv, texture=tex)
+    assert np.array_equal(r["rgb"][0], np.tile(tex, (2, 2, 1)))
+    uv3 = uv - 5.0                                                        # negative coordinates wrap the same way
+    r3 = oracle.render_scene(v, idx, cam()[None], H, W, uvs=uv3, texture=tex)
+    assert np.array_equal(r3["rgb"][0], np.tile(tex, (2, 2, 1)))
+    flat = np.full((4, 4, 3), (9, 99, 199), np.uint8)
+    r2 = oracle.render_scene(v, idx, cam()[None], H, W, uvs=uv * 7.3, texture=flat)
+    assert np.all(r2["rgb"][0] == np.array([9, 99, 199], np.uint8))
+
+
+def test_texture_coordinates_are_perspective_correct():
+    """Receding floor: the texel column must follow the ray-cast hit point, not an affine guess."""
+    v = np.array([[-40, -1, 0], [40, -1, 0], [40, -1, -32], [-40, -1, -32]], np.float32)
+    uv = np.array([[0, 0], [1, 0], [1, 1], [0, 1]], np.float32)          # v runs with distance, 32 m per repeat
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    tex = np.zeros((32, 4, 3), np.uint8)
+    tex[:, :, 0] = np.arange(32)[:, None] * 8                             # red encodes the row = metres from the camera
+    M = cam(far=100.0)
+    r = oracle.render_scene(v, idx, M[None], 64, 64, uvs=uv, texture=tex)
+    hit = r["tri_id"][0] != NOHIT
+    assert hit.sum() > 1000
+    # depth along the view axis == distance in -z here; level 0 as long as a pixel sees < 2 texel rows
+    near = hit & (r["depth"][0] < 6.0)
+    expect_row = np.floor(r["depth"][0]).astype(int)
+    got_row = r["rgb"][0][..., 0].astype(int) // 8
+    frac = r["depth"][0] - np.floor(r["depth"][0])
+    safe = near & (frac > 0.02) & (frac < 0.98)
+    assert safe.sum() > 300
+    assert np.array_equal(got_row[safe], expect_row[safe])
+
+
+def test_mip_level_uses_the_uv_area_of_a_sheared_mapping():
+    """uv = A p with det(A) = 3 texel areas per pixel area at level 0 (level 0 expected); a wrong
+    cross product (e.g. du1 dv1 - du2 dv2, which gives 6) would pick level 1 and other texels."""
+    H = W = 32
+    rng = np.random.default_rng(12)
+    tex = rng.integers(0, 256, (W, W, 3)).astype(np.uint8)
+    k = math.sqrt(3.0 / 5.0)
+    A = np.array([[2.0, 1.0], [1.0, 3.0]]) * k
+    corners = np.array([[0, 0], [1, 0], [1, 1], [0, 1]], np.float64)          # frame coordinates of the quad's corners
+    uv = (corners @ A.T).astype(np.float32)
+    v = _corner_quad(2.0, W, H)
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    r = oracle.render_scene(v, idx, cam()[None], H, W, uvs=uv, texture=tex)
+    jj, ii = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    p = np.stack([(ii + 0.5) / W, (jj + 0.5) / H], -1)
+    uvp = p @ A.T
+    fr = uvp - np.floor(uvp)
+    tx, ty = fr[..., 0] * W, fr[..., 1] * W
+    safe = (np.abs(tx - np.round(tx)) > 1e-2) & (np.abs(ty - np.round(ty)) > 1e-2)
+    expect = tex[np.minimum(ty.astype(int), W - 1), np.minimum(tx.astype(int), W - 1)]
+    assert safe.mean() > 0.9
+    assert np.array_equal(r["rgb"][0][safe], expect[safe])
