@@ -37,13 +37,14 @@ def full_stream_bytes(w):
     return geo + out + w.B * 68
 
 
-def cpu_baseline(w, n_envs):
+def cpu_baseline(w, n_envs, textured=False):
     """Time the CPU oracle, as it stands, on a strided sample of the same workload."""
     import oracle
     stride = max(1, w.B // n_envs)
     sel = np.arange(0, w.B, stride)[:n_envs]
     t0 = time.perf_counter()
-    r = oracle.render_batch(w.scenes, w.scene_ids[sel], w.view_proj[sel], w.H, w.W, rgbd=w.rgbd)
+    r = oracle.render_batch(w.scenes, w.scene_ids[sel], w.view_proj[sel], w.H, w.W, rgbd=w.rgbd,
+                            textured=textured and w.rgbd)
     dt = time.perf_counter() - t0
     return dict(value=len(sel) / dt, unit="frames/s", cores=int(r["threads"]), kind="oracle",
                 sample=f"{len(sel)} of {w.B} environments (every {stride}th), same scenes and matrices, {dt:.2f} s wall")
@@ -59,10 +60,13 @@ def measured_traffic(key):
         return None
 
 
-def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False):
+def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False, textured=False):
     mode = bps.MODE_RGBD if w.rgbd else bps.MODE_DEPTH
     r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, mode=mode, splits=splits, threads=threads, flags=flags)
-    handles = [r.load_scene(s.vertices, s.indices, s.colors if w.rgbd else None) for s in w.scenes]
+    if textured and w.rgbd:
+        handles = [r.load_scene_textured(s.vertices, s.indices, s.uvs, s.texture) for s in w.scenes]
+    else:
+        handles = [r.load_scene(s.vertices, s.indices, s.colors if w.rgbd else None) for s in w.scenes]
     ids = np.array([handles[k] for k in w.scene_ids], np.int32)
     vp = torch.from_numpy(w.view_proj).cuda()
     depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
@@ -179,6 +183,8 @@ def main():
     ap.add_argument("--no-occlusion", action="store_true", help="frustum culling of clusters only")
     ap.add_argument("--no-dispatch-order", action="store_true", help="launch work-groups in batch order")
     ap.add_argument("--sweep", action="store_true", help="batch-size x resolution sweep instead of the single benchmark line")
+    ap.add_argument("--textured", action="store_true",
+                    help="RGB-D workloads: colour from each scene's texture (uv + mip pyramid) instead of vertex colours")
     ap.add_argument("--rotate", action="store_true", help="also time rendering while scenes are being replaced")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed run: no diagnostics request, no full-stream run (for profiler runs)")
@@ -218,7 +224,7 @@ def main():
              (bps.FLAG_NO_DISPATCH_ORDER if args.no_dispatch_order else 0))
     culling = not args.no_cull
     main_run = timed_run(bps, torch, w, flags, args.steps, args.warmup, args.splits, args.threads,
-                         diagnostics=culling and not args.no_extras)
+                         diagnostics=culling and not args.no_extras, textured=args.textured)
     dt = main_run["dt"]
     kernel_ms_avg = main_run["kernel_ms_avg"]
     variant = "full_stream" if args.no_cull else ("frustum_cull" if args.no_occlusion else "cull")
@@ -268,7 +274,7 @@ def main():
         "config": {
             "workload": f"config{w.number}: {len(w.scenes)} procedural {'multi-room' if w.number > 1 else 'room'} scenes x "
                         f"~{w.scenes[0].T} triangles, {w.B} environments (scene = b mod {len(w.scenes)}), "
-                        f"{w.H}x{w.W} {'RGB-D' if w.rgbd else 'float32 depth'}",
+                        f"{w.H}x{w.W} {('textured RGB-D' if args.textured else 'RGB-D') if w.rgbd else 'float32 depth'}",
             "variant": variant,
             "B": w.B, "H": w.H, "W": w.W, "scenes": len(w.scenes),
             "triangles_per_scene": [s.T for s in w.scenes],
@@ -284,7 +290,8 @@ def main():
         out["roofline"]["launches_timed"] = main_run["launches"]
     if culling and not args.no_extras:
         steps2 = max(5, args.steps // 5)
-        fs = timed_run(bps, torch, w, bps.FLAG_NO_CLUSTER_CULL, steps2, 3, args.splits, args.threads)
+        fs = timed_run(bps, torch, w, bps.FLAG_NO_CLUSTER_CULL, steps2, 3, args.splits, args.threads,
+                       textured=args.textured)
         rl = roofline(fbytes, fs["kernel_ms_avg"],
                       "full stream: 12 B/triangle + 12 B/vertex per environment + output + request; same request "
                       "with cluster culling switched off", f"config{w.number}_full_stream")
@@ -294,7 +301,7 @@ def main():
     if args.rotate and not w.rgbd:
         out["rotation"] = rotation_run(bps, torch, w, max(2000, args.steps), args.warmup)
     if args.cpu_envs > 0:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_envs)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_envs, args.textured)
     print(json.dumps(out))
 
 

@@ -99,6 +99,20 @@ bps_status bps_load_scene_async(bps_renderer *r, const float *vertices, uint32_t
                                 uint32_t T, const uint8_t *colors, void *copy_stream, bps_scene *out_handle);
 bps_status bps_scene_ready(bps_renderer *r, bps_scene scene, int32_t *ready);
 
+/* Textured scene (the paper's RGB sensor renders textured scans, Sec. 4.1).  As bps_load_scene,
+ * with per-vertex texture coordinates and one RGB8 texture per scene instead of vertex colours:
+ *   uvs     float32 [V][2]              texture coordinates, any range (the texture repeats)
+ *   texels  uint8   [tex_h][tex_w][3]   tex_w, tex_h powers of two up to 4096
+ * In RGB-D mode a pixel then shows one texel, chosen as follows: (u, v) are interpolated
+ * perspective-correctly like colours; the library builds a mip pyramid (each level halves both
+ * sides, a texel is (a+b+c+d+2)>>2 of its 2x2 parents); each rasterised triangle uses the level
+ * at which one pixel covers fewer than four texels (from its uv area and pixel area); the texel
+ * is the one containing (u - floor u, v - floor v).  copy_stream NULL = wait for the upload,
+ * otherwise the copy is only enqueued there (see bps_load_scene_async). */
+bps_status bps_load_scene_textured(bps_renderer *r, const float *vertices, uint32_t V, const uint32_t *indices,
+                                   uint32_t T, const float *uvs, const uint8_t *texels, uint32_t tex_w,
+                                   uint32_t tex_h, void *copy_stream, bps_scene *out_handle);
+
 /* Host-only helper (no GPU needed): re-pack a mesh exactly as bps_load_scene does and copy the
  * cluster arrays out, for tests and tools.  On entry *count is the capacity of the output
  * arrays in clusters (ignored when all three are NULL); on return it is the cluster count.

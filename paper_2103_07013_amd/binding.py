@@ -12,7 +12,7 @@ MODE_DEPTH, MODE_RGBD = 0, 1
 FLAG_NO_CLUSTER_CULL = 1
 FLAG_NO_OCCLUSION_CULL = 2
 FLAG_NO_DISPATCH_ORDER = 4
-EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
+EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_load_scene_textured", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
            "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 
 
@@ -48,6 +48,9 @@ def load_library():
     lib.bps_load_scene.argtypes = [vp, vp, ctypes.c_uint32, vp, ctypes.c_uint32, vp, ctypes.POINTER(ctypes.c_int32)]
     lib.bps_load_scene_async.restype = ctypes.c_int32
     lib.bps_load_scene_async.argtypes = [vp, vp, ctypes.c_uint32, vp, ctypes.c_uint32, vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.bps_load_scene_textured.restype = ctypes.c_int32
+    lib.bps_load_scene_textured.argtypes = [vp, vp, ctypes.c_uint32, vp, ctypes.c_uint32, vp, vp, ctypes.c_uint32,
+                                            ctypes.c_uint32, vp, ctypes.POINTER(ctypes.c_int32)]
     lib.bps_scene_ready.restype = ctypes.c_int32
     lib.bps_scene_ready.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.bps_pack_clusters.restype = ctypes.c_int32
@@ -120,6 +123,23 @@ def bps_load_scene_async(handle, vertices, indices, colors=None, copy_stream=Non
     out = ctypes.c_int32(-1)
     _check(lib.bps_load_scene_async(handle, v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0],
                                     None if c is None else c.ctypes.data, ctypes.c_void_p(s or 0), ctypes.byref(out)), handle)
+    return int(out.value)
+
+
+def bps_load_scene_textured(handle, vertices, indices, uvs, texture, copy_stream=None):
+    """vertices f32 [V,3], indices u32 [T,3], uvs f32 [V,2], texture u8 [h,w,3] with power-of-two sides."""
+    lib = load_library()
+    v = np.ascontiguousarray(vertices, np.float32).reshape(-1, 3)
+    i = np.ascontiguousarray(indices, np.uint32).reshape(-1, 3)
+    uv = np.ascontiguousarray(uvs, np.float32).reshape(-1, 2)
+    tex = np.ascontiguousarray(texture, np.uint8)
+    if uv.shape[0] != v.shape[0] or tex.ndim != 3 or tex.shape[2] != 3:
+        raise ValueError("uvs must have one row per vertex and texture must be [h,w,3]")
+    s = copy_stream if isinstance(copy_stream, int) or copy_stream is None else copy_stream.cuda_stream
+    out = ctypes.c_int32(-1)
+    _check(lib.bps_load_scene_textured(handle, v.ctypes.data, v.shape[0], i.ctypes.data, i.shape[0], uv.ctypes.data,
+                                       tex.ctypes.data, tex.shape[1], tex.shape[0], ctypes.c_void_p(s or 0),
+                                       ctypes.byref(out)), handle)
     return int(out.value)
 
 
@@ -236,6 +256,9 @@ class Renderer:
 
     def load_scene(self, vertices, indices, colors=None):
         return bps_load_scene(self.handle, vertices, indices, colors)
+
+    def load_scene_textured(self, vertices, indices, uvs, texture, copy_stream=None):
+        return bps_load_scene_textured(self.handle, vertices, indices, uvs, texture, copy_stream)
 
     def load_scene_async(self, vertices, indices, colors=None, copy_stream=None):
         return bps_load_scene_async(self.handle, vertices, indices, colors, copy_stream)

@@ -301,12 +301,24 @@ void bps_destroy(bps_renderer* r) {
 
 namespace {
 
+struct TextureArg {
+    const float* uvs = nullptr;        // [V][2]
+    const uint8_t* texels = nullptr;   // [h][w][3]
+    uint32_t w = 0, h = 0;
+};
+
 // Shared by the synchronous and asynchronous entry points: validate, cluster, lay every array out
 // in one pinned image, copy it into one device block on `stream`, update the scene table on the
 // same stream and record the scene's ready event.
 bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
-                         const uint8_t* colors, hipStream_t stream, bps_scene* out_handle) {
+                         const uint8_t* colors, const TextureArg& tex, hipStream_t stream, bps_scene* out_handle) {
     if (!vertices || !indices || !out_handle) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: null argument");
+    const bool textured = tex.uvs != nullptr || tex.texels != nullptr;
+    if (textured) {
+        if (!tex.uvs || !tex.texels) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: uvs and texels go together");
+        if (tex.w == 0 || tex.h == 0 || tex.w > 4096 || tex.h > 4096 || (tex.w & (tex.w - 1)) || (tex.h & (tex.h - 1)))
+            return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: texture sides must be powers of two up to 4096 (got %ux%u)", tex.w, tex.h);
+    }
     if (V == 0 || T == 0) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: empty mesh (V=%u, T=%u)", V, T);
     for (size_t i = 0; i < 3 * (size_t)T; ++i)
         if (indices[i] >= V)
@@ -331,6 +343,16 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
     const size_t o_cverts = place(cs.verts.size() * 4), o_ctris = place(cs.tris.size() * 4), o_ids = place(cs.tri_id.size() * 4);
     const size_t o_verts = place((size_t)V * 12), o_idx = place((size_t)T * 12), o_col = colors ? place((size_t)V * 3) : 0;
     const size_t o_cb = place((size_t)6 * c_stride * 4), o_bb = place((size_t)6 * nblocks * 4);
+    // texture: uv per vertex, then every mip level as RGBA8 texels, level after level
+    size_t pyramid_texels = 0;
+    uint32_t tex_levels = 0;
+    if (textured)
+        for (uint32_t a_ = tex.w, b_ = tex.h;; a_ = a_ > 1 ? a_ / 2 : 1, b_ = b_ > 1 ? b_ / 2 : 1) {
+            pyramid_texels += (size_t)a_ * b_;
+            ++tex_levels;
+            if (a_ == 1 && b_ == 1) break;
+        }
+    const size_t o_uv = textured ? place((size_t)V * 8) : 0, o_tex = textured ? place(pyramid_texels * 4) : 0;
     const size_t dev_bytes = off;
     const size_t o_rec = place(sizeof(bps::SceneDev));
     const size_t img_bytes = off;
@@ -360,6 +382,36 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
     std::memcpy(img + o_verts, vertices, (size_t)V * 12);
     std::memcpy(img + o_idx, indices, (size_t)T * 12);
     if (colors) std::memcpy(img + o_col, colors, (size_t)V * 3);
+    if (textured) {
+        std::memcpy(img + o_uv, tex.uvs, (size_t)V * 8);
+        // mip pyramid: every level halves both sides (not below 1); a texel is (a + b + c + d + 2) >> 2
+        // of its 2x2 parents, parents clamped at the border
+        uint8_t* lvl = img + o_tex;
+        uint32_t pw = tex.w, ph = tex.h;
+        for (size_t i = 0; i < (size_t)pw * ph; ++i) {
+            lvl[4 * i + 0] = tex.texels[3 * i + 0];
+            lvl[4 * i + 1] = tex.texels[3 * i + 1];
+            lvl[4 * i + 2] = tex.texels[3 * i + 2];
+            lvl[4 * i + 3] = 255;
+        }
+        for (uint32_t l = 1; l < tex_levels; ++l) {
+            const uint8_t* prev = lvl;
+            lvl += (size_t)pw * ph * 4;
+            const uint32_t lw = pw > 1 ? pw / 2 : 1, lh = ph > 1 ? ph / 2 : 1;
+            for (uint32_t y = 0; y < lh; ++y)
+                for (uint32_t x = 0; x < lw; ++x) {
+                    const uint32_t x0 = std::min(2 * x, pw - 1), x1 = std::min(2 * x + 1, pw - 1);
+                    const uint32_t y0 = std::min(2 * y, ph - 1), y1 = std::min(2 * y + 1, ph - 1);
+                    for (int ch = 0; ch < 4; ++ch) {
+                        uint32_t sum = prev[4 * ((size_t)y0 * pw + x0) + ch] + prev[4 * ((size_t)y0 * pw + x1) + ch] +
+                                       prev[4 * ((size_t)y1 * pw + x0) + ch] + prev[4 * ((size_t)y1 * pw + x1) + ch];
+                        lvl[4 * ((size_t)y * lw + x) + ch] = (uint8_t)((sum + 2) >> 2);
+                    }
+                }
+            pw = lw;
+            ph = lh;
+        }
+    }
     {   // bounds as six planes so that 64 lanes read 64 consecutive clusters (or blocks of 64 clusters)
         float* cb = (float*)(img + o_cb);
         float* bb = (float*)(img + o_bb);
@@ -413,13 +465,18 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
     HostScene hs;
     hs.arena = arena;
     hs.bytes = dev_bytes;
-    hs.has_colors = colors != nullptr;
+    hs.has_colors = colors != nullptr || textured;
     hs.dev.cverts = (const float*)(d + o_cverts);
     hs.dev.ctris = (const uint32_t*)(d + o_ctris);
     hs.dev.ctri_id = (const uint32_t*)(d + o_ids);
     hs.dev.verts = (const float*)(d + o_verts);
     hs.dev.indices = (const uint32_t*)(d + o_idx);
     hs.dev.colors = colors ? (const uint8_t*)(d + o_col) : nullptr;
+    hs.dev.uvs = textured ? (const float*)(d + o_uv) : nullptr;
+    hs.dev.texels = textured ? (const uint32_t*)(d + o_tex) : nullptr;
+    hs.dev.tex_w = textured ? tex.w : 0;
+    hs.dev.tex_h = textured ? tex.h : 0;
+    hs.dev.tex_levels = tex_levels;
     hs.dev.cbounds = (const float*)(d + o_cb);
     hs.dev.bbounds = (const float*)(d + o_bb);
     hs.dev.n_clusters = cs.count;
@@ -456,7 +513,7 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
 bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
                           const uint8_t* colors, bps_scene* out_handle) {
     if (!r) return BPS_ERR_INVALID_ARG;
-    bps_status st = load_scene_on(r, vertices, V, indices, T, colors, r->load_stream, out_handle);
+    bps_status st = load_scene_on(r, vertices, V, indices, T, colors, TextureArg{}, r->load_stream, out_handle);
     if (st != BPS_OK) return st;
     BPS_HIP(r, hipStreamSynchronize(r->load_stream));
     std::lock_guard<std::mutex> lock(r->mu);
@@ -469,7 +526,28 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
 bps_status bps_load_scene_async(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
                                 const uint8_t* colors, void* copy_stream, bps_scene* out_handle) {
     if (!r) return BPS_ERR_INVALID_ARG;
-    return load_scene_on(r, vertices, V, indices, T, colors, (hipStream_t)copy_stream, out_handle);
+    return load_scene_on(r, vertices, V, indices, T, colors, TextureArg{}, (hipStream_t)copy_stream, out_handle);
+}
+
+bps_status bps_load_scene_textured(bps_renderer* r, const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T,
+                                   const float* uvs, const uint8_t* texels, uint32_t tex_w, uint32_t tex_h,
+                                   void* copy_stream, bps_scene* out_handle) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    if (!uvs || !texels) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene_textured: null uvs or texels");
+    TextureArg tex;
+    tex.uvs = uvs;
+    tex.texels = texels;
+    tex.w = tex_w;
+    tex.h = tex_h;
+    hipStream_t stream = copy_stream ? (hipStream_t)copy_stream : r->load_stream;
+    bps_status st = load_scene_on(r, vertices, V, indices, T, nullptr, tex, stream, out_handle);
+    if (st != BPS_OK || copy_stream) return st;
+    BPS_HIP(r, hipStreamSynchronize(r->load_stream));
+    std::lock_guard<std::mutex> lock(r->mu);
+    HostScene& hs = r->scenes[*out_handle];
+    if (hs.ready) (void)hipEventDestroy(hs.ready);
+    hs.ready = nullptr;
+    return BPS_OK;
 }
 
 bps_status bps_scene_ready(bps_renderer* r, bps_scene scene, int32_t* ready) {

@@ -31,6 +31,9 @@ struct SceneDev {
     const float* verts;        // [V][3]     original arrays, used when shading
     const uint32_t* indices;   // [T][3]
     const uint8_t* colors;     // [V][3] or null
+    const float* uvs;          // [V][2] or null (textured scenes)
+    const uint32_t* texels;    // RGBA8 mip pyramid, level after level, or null
+    uint32_t tex_w, tex_h, tex_levels, pad2;
     uint32_t n_clusters, n_tris, n_verts, c_stride, b_stride, pad;
 };
 

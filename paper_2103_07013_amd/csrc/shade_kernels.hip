@@ -24,7 +24,7 @@ struct SVert {
 
 // Colour of pixel (i, j) from one snapped fan triangle; returns false when it does not cover the pixel.
 __device__ __forceinline__ bool piece_colour(const SVert& v0, const SVert& v1, const SVert& v2, int i, int j,
-                                             float& depth, float (&rgb)[3]) {
+                                             float& depth, float (&rgb)[3], float& uv_area2, int& area2) {
     Setup s = make_setup(v0.xy, v1.xy, v2.xy, v0.iw, v1.iw, v2.iw);
     if (s.A2 == 0) return false;
     const SVert& a = v0;
@@ -42,6 +42,10 @@ __device__ __forceinline__ bool piece_colour(const SVert& v0, const SVert& v1, c
     rgb[0] = fmaf(w2, c.r, fmaf(w1, b.r, w0 * a.r)) / num;
     rgb[1] = fmaf(w2, c.g, fmaf(w1, b.g, w0 * a.g)) / num;
     rgb[2] = fmaf(w2, c.b, fmaf(w1, b.b, w0 * a.b)) / num;
+    // for textured scenes slots r, g hold (u, v): twice the triangle's uv area over its pixel area
+    float du1 = b.r - a.r, dv1 = b.g - a.g, du2 = c.r - a.r, dv2 = c.g - a.g;
+    uv_area2 = fabsf(fmaf(du1, dv2, -(du2 * dv1)));
+    area2 = s.A2;
     return true;
 }
 
@@ -65,7 +69,8 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
     uint8_t out[3] = {0, 0, 0};
     const uint32_t id = tri_id[p];
     const SceneDev sc = scenes[env_scene[env]];
-    if (id != 0xFFFFFFFFu && sc.colors != nullptr && id < sc.n_tris) {
+    const bool textured = sc.texels != nullptr;
+    if (id != 0xFFFFFFFFu && (sc.colors != nullptr || textured) && id < sc.n_tris) {
         float M[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) M[k] = view_proj[(size_t)env * 16 + k];
@@ -75,10 +80,16 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
             uint32_t vi = sc.indices[3 * (size_t)id + k];
             const float* v = sc.verts + 3 * (size_t)vi;
             poly[0][k].c = to_clip(M, v[0], v[1], v[2]);
-            const uint8_t* col = sc.colors + 3 * (size_t)vi;
-            poly[0][k].r = (float)col[0];
-            poly[0][k].g = (float)col[1];
-            poly[0][k].b = (float)col[2];
+            if (textured) {
+                poly[0][k].r = sc.uvs[2 * (size_t)vi + 0];
+                poly[0][k].g = sc.uvs[2 * (size_t)vi + 1];
+                poly[0][k].b = 0.0f;
+            } else {
+                const uint8_t* col = sc.colors + 3 * (size_t)vi;
+                poly[0][k].r = (float)col[0];
+                poly[0][k].g = (float)col[1];
+                poly[0][k].b = (float)col[2];
+            }
             oc_or |= outcode(poly[0][k].c);
         }
         int cnt = 3, cur = 0;
@@ -131,13 +142,36 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
                 float best = 0.0f;
                 bool found = false;
                 for (int q = 1; q + 1 < cnt; ++q) {
-                    float d, rgb[3];
-                    if (piece_colour(sv[0], sv[q], sv[q + 1], i, j, d, rgb) && (!found || d < best)) {
+                    float d, rgb[3], uv_area2;
+                    int area2;
+                    if (piece_colour(sv[0], sv[q], sv[q + 1], i, j, d, rgb, uv_area2, area2) && (!found || d < best)) {
                         found = true;
                         best = d;
-                        out[0] = to_u8(rgb[0]);
-                        out[1] = to_u8(rgb[1]);
-                        out[2] = to_u8(rgb[2]);
+                        if (textured) {
+                            // mip level: quarter the texels-per-pixel ratio while it is at least 4
+                            float ratio = ((uv_area2 * (float)sc.tex_w) * (float)sc.tex_h) * 65536.0f / (float)area2;
+                            uint32_t L = 0, lw = sc.tex_w, lh = sc.tex_h;
+                            size_t off = 0;
+                            while (L + 1 < sc.tex_levels && ratio >= 4.0f) {
+                                ratio *= 0.25f;
+                                off += (size_t)lw * lh;
+                                lw = lw > 1 ? lw / 2 : 1;
+                                lh = lh > 1 ? lh / 2 : 1;
+                                ++L;
+                            }
+                            float fu = rgb[0] - floorf(rgb[0]), fv = rgb[1] - floorf(rgb[1]);
+                            if (!(fu >= 0.0f && fu < 1.0f)) fu = 0.0f;
+                            if (!(fv >= 0.0f && fv < 1.0f)) fv = 0.0f;
+                            uint32_t x = min((uint32_t)(fu * (float)lw), lw - 1), y = min((uint32_t)(fv * (float)lh), lh - 1);
+                            uint32_t texel = sc.texels[off + (size_t)y * lw + x];
+                            out[0] = (uint8_t)(texel & 0xFFu);
+                            out[1] = (uint8_t)((texel >> 8) & 0xFFu);
+                            out[2] = (uint8_t)((texel >> 16) & 0xFFu);
+                        } else {
+                            out[0] = to_u8(rgb[0]);
+                            out[1] = to_u8(rgb[1]);
+                            out[2] = to_u8(rgb[2]);
+                        }
                     }
                 }
             }

@@ -185,3 +185,54 @@ def test_supersampled_output_is_the_box_filter_of_the_double_resolution_render(r
             assert np.array_equal(rgb.cpu().numpy().astype(np.int32), ec)
         with pytest.raises(bps.BpsError):
             r.render(ids, w.view_proj, want_tri_id=True)
+
+
+@pytest.mark.parametrize("cfg,B,scale,H,W", [(4, 16, 0.02, 64, 64), (1, 32, 1.0, 64, 64), (4, 6, 0.05, 96, 128)])
+def test_textured_scenes_match_oracle_texels(cfg, B, scale, H, W):
+    """Texture coordinates interpolated (and clipped) like colours, one mip level per rasterised
+    triangle, nearest texel: the same float sequence as the oracle, so every byte is equal."""
+    import torch
+    import oracle
+    import paper_2103_07013_amd as bps
+    w = synth.build_config(cfg, B=B, scale=scale)
+    ref = oracle.render_batch(w.scenes, w.scene_ids, w.view_proj, H, W, rgbd=True, textured=True)
+    with bps.Renderer(max_batch=w.B, height=H, width=W, mode=bps.MODE_RGBD) as r:
+        hs = [r.load_scene_textured(s.vertices, s.indices, s.uvs, s.texture) for s in w.scenes]
+        ids = np.array([hs[k] for k in w.scene_ids], np.int32)
+        depth, rgb, tid = r.render(ids, w.view_proj, want_tri_id=True)
+        torch.cuda.synchronize()
+    assert np.array_equal(tid.cpu().numpy().view(np.uint32), ref["tri_id"])
+    grgb = rgb.cpu().numpy()
+    assert np.array_equal(grgb, ref["rgb"])
+    hit = ref["tri_id"] != NOHIT
+    assert len(np.unique(grgb[hit].reshape(-1, 3), axis=0)) > 50      # really texels, not flat colours
+
+
+def test_textured_and_coloured_scenes_mix_in_one_batch_and_odd_textures_work():
+    """One batch may reference textured and vertex-coloured scenes; a 1x1 and a 4x64 texture are
+    legal (all levels clamp at 1 texel per side); uv far outside [0,1) wraps."""
+    import torch
+    import oracle
+    import paper_2103_07013_amd as bps
+    w = synth.build_config(1, B=12)
+    s = w.scenes[0]
+    rng = np.random.default_rng(5)
+    texA = rng.integers(0, 256, size=(64, 4, 3)).astype(np.uint8)
+    texB = np.array([[[9, 200, 31]]], np.uint8)
+    uvA = (s.uvs * 7.5 - 40.0).astype(np.float32)
+    refA = oracle.render_scene(s.vertices, s.indices, w.view_proj[:4], 64, 64, uvs=uvA, texture=texA)
+    refB = oracle.render_scene(s.vertices, s.indices, w.view_proj[4:8], 64, 64, uvs=s.uvs, texture=texB)
+    refC = oracle.render_scene(s.vertices, s.indices, w.view_proj[8:], 64, 64, colors=s.colors)
+    with bps.Renderer(max_batch=12, mode=bps.MODE_RGBD) as r:
+        a = r.load_scene_textured(s.vertices, s.indices, uvA, texA)
+        b = r.load_scene_textured(s.vertices, s.indices, s.uvs, texB)
+        c = r.load_scene(s.vertices, s.indices, s.colors)
+        ids = np.array([a] * 4 + [b] * 4 + [c] * 4, np.int32)
+        depth, rgb, _ = r.render(ids, w.view_proj)
+        torch.cuda.synchronize()
+        with pytest.raises(bps.BpsError):
+            r.load_scene_textured(s.vertices, s.indices, s.uvs, np.zeros((48, 64, 3), np.uint8))   # 48: not 2^k
+    g = rgb.cpu().numpy()
+    assert np.array_equal(g[:4], refA["rgb"])
+    assert np.array_equal(g[4:8], refB["rgb"])
+    assert np.array_equal(g[8:], refC["rgb"])
