@@ -93,8 +93,9 @@ __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n);
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch);
-// Fills dispatch[n_items] with the item indices in launch order (costliest first within each die's share).
-constexpr uint32_t kMaxPlannedItems = 16384;   // k_dispatch_order keeps one cost word per item in LDS
+// Fills dispatch[n_items] with the item indices in launch order, costliest first; cost is scratch,
+// one word per item.
+constexpr uint32_t kMaxPlannedItems = 16384;
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
                  const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch);
 hipError_t prepare_raster(int threads, size_t lds);

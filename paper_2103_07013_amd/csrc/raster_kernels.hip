@@ -755,8 +755,7 @@ __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float
 // Launch planning.  Work-groups are dispatched in index order, so handing out the most expensive
 // items first (longest processing time first) shortens the tail of the launch.  An item's cost
 // is estimated as the number of its scene's 64-cluster blocks that are not wholly outside the
-// environment's frustum; k_dispatch_order then ranks the items of each die's share (index % 8)
-// by decreasing cost.
+// environment's frustum; k_dispatch_order then sorts all items by decreasing cost.
 __global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                   const float* __restrict__ view_proj, FrameParams fp, uint32_t n_items,
                                                   uint32_t* __restrict__ cost) {
@@ -791,26 +790,52 @@ __global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ s
     if (threadIdx.x == 0) cost[i] = count;
 }
 
+// Dispatch order = all items by decreasing estimated cost (counting sort over 2048 linear cost
+// buckets): consecutive work-group indices go to consecutive dies, so every die receives an even
+// sample of the cost distribution, costliest first.
 __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restrict__ cost, uint32_t n_items,
                                                          uint32_t* __restrict__ dispatch) {
-    extern __shared__ uint32_t s_cost[];
-    for (uint32_t i = threadIdx.x; i < n_items; i += blockDim.x) s_cost[i] = cost[i];
+    constexpr uint32_t kBuckets = 2048;
+    __shared__ uint32_t bucket[kBuckets];
+    __shared__ uint32_t scan[1024];
+    __shared__ uint32_t largest;
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t b = tid; b < kBuckets; b += 1024u) bucket[b] = 0u;
+    if (tid == 0) largest = 0u;
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < n_items; i += blockDim.x) {
-        const uint32_t die = i & 7u, mine = s_cost[i];
-        uint32_t rank = 0;
-        for (uint32_t o = die; o < n_items; o += 8u) {
-            const uint32_t c = s_cost[o];
-            rank += (c > mine || (c == mine && o < i)) ? 1u : 0u;
-        }
-        dispatch[die + 8u * rank] = i;
+    {
+        uint32_t mx = 0;
+        for (uint32_t i = tid; i < n_items; i += 1024u) mx = max(mx, cost[i]);
+        atomicMax(&largest, mx);
     }
+    __syncthreads();
+    const float scale = largest ? (float)(kBuckets - 1) / (float)largest : 0.0f;
+    auto bucket_of = [&](uint32_t i) -> uint32_t {      // bucket 0 holds the costliest items
+        return kBuckets - 1u - min((uint32_t)((float)cost[i] * scale), kBuckets - 1u);
+    };
+    for (uint32_t i = tid; i < n_items; i += 1024u) atomicAdd(&bucket[bucket_of(i)], 1u);
+    __syncthreads();
+    // exclusive prefix sum over the buckets: two per thread, then a scan over the 1024 pair sums
+    const uint32_t a0 = bucket[2 * tid], a1 = bucket[2 * tid + 1];
+    scan[tid] = a0 + a1;
+    __syncthreads();
+    for (uint32_t step = 1; step < 1024u; step <<= 1) {
+        const uint32_t v = tid >= step ? scan[tid - step] : 0u;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+    }
+    const uint32_t before = scan[tid] - (a0 + a1);
+    bucket[2 * tid] = before;
+    bucket[2 * tid + 1] = before + a0;
+    __syncthreads();
+    for (uint32_t i = tid; i < n_items; i += 1024u) dispatch[atomicAdd(&bucket[bucket_of(i)], 1u)] = i;
 }
 
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
                  const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch) {
     hipLaunchKernelGGL(k_item_cost, dim3(n_items), dim3(64), 0, stream, scenes, items, view_proj, fp, n_items, cost);
-    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), n_items * sizeof(uint32_t), stream, cost, n_items, dispatch);
+    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), 0, stream, cost, n_items, dispatch);
 }
 
 __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n) {
