@@ -161,6 +161,9 @@ bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total
  *   [9..15] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
  *           in the bounds testing, barrier, depth sort, (unused), cluster processing, barrier
  *           and flush phases.
+ *   with enable = 1 instead: [11] environment index, [12] run times of all the group's wavefronts
+ *           summed, [13] start and [14] end of the group on the device-wide 100 MHz clock (low 32
+ *           bits), [15] hardware id of the compute unit that ran it (die in the top byte).
  * `capacity` is the room in `out` (in words), *written the number of words copied. */
 bps_status bps_set_diagnostics(bps_renderer *r, int32_t enable);
 bps_status bps_read_diagnostics(bps_renderer *r, uint64_t *out, uint32_t capacity, uint32_t *written);

@@ -714,6 +714,20 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         rec[0] = st_tested; rec[1] = st_boxed; rec[2] = st_drawn; rec[3] = st_straddle; rec[4] = st_hidden; rec[5] = dt;
         rec[6] = tally[0]; rec[7] = tally[1]; rec[8] = st_hiz;
         for (int k = 1; k < 8; ++k) rec[8 + k] = ticks[k];
+        if (!fp.phase_timers) {
+            // without phase timers the last words tell where and when the group ran: the sum of the
+            // wavefronts' durations (against word 5: how unevenly they finish), the environment, start
+            // and end on the device-wide 100 MHz clock, and the hardware id (compute unit, shader
+            // engine in the low 24 bits, die above)
+            rec[12] = dt;
+            if (wave == 0) {
+                rec[11] = item.env;
+                rec[13] = (uint32_t)t_start;
+                rec[14] = (uint32_t)wall_clock64();
+                rec[15] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) & 0xFFFFFFu) |
+                          (__builtin_amdgcn_s_getreg((3 << 11) | 20) << 24);
+            }
+        }
     }
     __syncthreads();
     if (stats && tid < 16) {
