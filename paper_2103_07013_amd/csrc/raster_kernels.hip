@@ -844,6 +844,47 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
     bucket[2 * tid + 1] = before + a0;
     __syncthreads();
     for (uint32_t i = tid; i < n_items; i += 1024u) dispatch[atomicAdd(&bucket[bucket_of(i)], 1u)] = i;
+    __syncthreads();
+    // Die affinity.  Position p of the order runs on die p % 8, and the host lays the items out so
+    // that item i's scene is mostly used by items with the same i % 8.  Within every run of 64
+    // consecutive positions (items of nearly equal cost, eight positions per die) the items are
+    // rearranged so that as many as possible land on their own die; each die still gets eight
+    // items of every cost class, but now finds its scenes in its own L2.
+    uint32_t* slot_item = scan;                       // [16 waves][64]: the window being rebuilt
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    for (uint32_t base = wave * 64u; base + 64u <= n_items; base += 1024u) {
+        const uint32_t item = dispatch[base + lane];
+        const uint32_t home = item & 7u;
+        uint32_t* mine = slot_item + wave * 64u;
+        mine[lane] = 0xFFFFFFFFu;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        bool placed = false;
+        for (uint32_t d = 0; d < 8u; ++d) {
+            const unsigned long long want = __builtin_amdgcn_ballot_w64(home == d);
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(want >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)want, 0u));
+            if (home == d && rank < 8u) {
+                mine[rank * 8u + d] = item;
+                placed = true;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // the rest take the free positions in order
+        const unsigned long long free_mask = __builtin_amdgcn_ballot_w64(mine[lane] == 0xFFFFFFFFu);
+        const unsigned long long left_mask = __builtin_amdgcn_ballot_w64(!placed);
+        if (!placed) {
+            uint32_t r = __builtin_amdgcn_mbcnt_hi((uint32_t)(left_mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)left_mask, 0u));
+            unsigned long long m = free_mask;
+            for (uint32_t k = 0; k < r; ++k) m &= m - 1ull;      // drop the r lowest free positions
+            mine[__builtin_ctzll(m)] = item;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        dispatch[base + lane] = mine[lane];
+    }
 }
 
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
