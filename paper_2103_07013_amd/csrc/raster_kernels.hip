@@ -642,8 +642,13 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             if (!can_project) oc |= kNoProject;
             const bool all_inside = ballot64(oc != 0) == 0;
             wave_lds_sync();   // earlier reads of the stage are done
-            L.stage[lane] = make_float2(__uint_as_float(xy), iw);
-            if (!all_inside) L.stage_oc[lane] = oc;
+            // the slot index is laundered so that its LDS address is recomputed here (one add) rather
+            // than kept in a register across the whole loop, where it was spilled and its reload
+            // made the wavefront wait for the cluster prefetch as well
+            int stage_slot = lane;
+            asm volatile("" : "+v"(stage_slot));
+            L.stage[stage_slot] = make_float2(__uint_as_float(xy), iw);
+            if (!all_inside) L.stage_oc[stage_slot] = oc;
             wave_lds_sync();
 
             // ---- triangle phase: two slots per lane
