@@ -78,7 +78,8 @@ __host__ __device__ inline size_t lds_bytes(int tile_h, int tile_w, int threads,
            2 * kDepthBins * 4 + kHizTiles * 4 + 32;
 }
 
-template <int NT>
+// DIAG = true is the instance launched while diagnostics are on; it alone keeps counters and timers.
+template <int NT, bool DIAG>
 __global__ void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                          const float* __restrict__ view_proj, FrameParams fp, unsigned long long* __restrict__ gvis,
                          float* __restrict__ out_depth, uint32_t* __restrict__ out_id,

@@ -367,13 +367,17 @@ __device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool wan
 }  // namespace
 
 // =============================================================================================
-template <int NT>
+template <int NT, bool DIAG>
 __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
-                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats,
+                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats_block,
                                                const uint32_t* __restrict__ dispatch) {
     extern __shared__ __align__(16) unsigned char smem[];
+    // The DIAG = false instance carries no counters or timers at all: everything below that feeds
+    // only the diagnostics record is dead code there and costs neither registers nor instructions.
+    unsigned long long* const stats = DIAG ? stats_block : nullptr;
+    const bool phase_timers = DIAG && fp.phase_timers != 0;
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -431,7 +435,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     // phase timers (diagnostics only): ticks[k] accumulates the time since the previous TICK
     unsigned long long t_prev = t_start, t_c0 = 0;
     uint32_t ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define TICK(k) do { if (fp.phase_timers) { unsigned long long t_ = wall_clock64(); ticks[k] += (uint32_t)(t_ - t_prev); t_prev = t_; } } while (0)
+#define TICK(k) do { if (phase_timers) { unsigned long long t_ = wall_clock64(); ticks[k] += (uint32_t)(t_ - t_prev); t_prev = t_; } } while (0)
 #define TICKC0() do { if (stats) t_c0 = wall_clock64(); } while (0)
 #define TICKC(k) do { if (stats) ticks[k] += (uint32_t)(wall_clock64() - t_c0); } while (0)
     const uint32_t full_tri_mask = 0x00FFFFFFu;
@@ -719,7 +723,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         rec[0] = st_tested; rec[1] = st_boxed; rec[2] = st_drawn; rec[3] = st_straddle; rec[4] = st_hidden; rec[5] = dt;
         rec[6] = tally[0]; rec[7] = tally[1]; rec[8] = st_hiz;
         for (int k = 1; k < 8; ++k) rec[8 + k] = ticks[k];
-        if (!fp.phase_timers) {
+        if (!phase_timers) {
             // without phase timers the last words tell where and when the group ran: the sum of the
             // wavefronts' durations (against word 5: how unevenly they finish), the environment, start
             // and end on the device-wide 100 MHz clock, and the hardware id (compute unit, shader
@@ -908,25 +912,39 @@ __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n) {
     if (p < n) gvis[p] = kEmptyKey;
 }
 
+namespace {
+template <bool DIAG>
+const void* raster_entry(int threads) {
+    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG>)
+           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG>)
+           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG>)
+                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG>);
+}
+}  // namespace
+
 hipError_t prepare_raster(int threads, size_t lds) {
-    const void* f = threads == 256   ? reinterpret_cast<const void*>(&k_raster<256>)
-                    : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384>)
-                    : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512>)
-                                     : reinterpret_cast<const void*>(&k_raster<1024>);
-    return hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute(raster_entry<false>(threads), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(raster_entry<true>(threads), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch) {
-    if (threads == 256)
-        hipLaunchKernelGGL(k_raster<256>, grid, dim3(256), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
-    else if (threads == 384)
-        hipLaunchKernelGGL(k_raster<384>, grid, dim3(384), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
-    else if (threads == 512)
-        hipLaunchKernelGGL(k_raster<512>, grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
-    else
-        hipLaunchKernelGGL(k_raster<1024>, grid, dim3(1024), lds, stream, scenes, items, view_proj, fp, gvis, out_depth, out_id, stats, dispatch);
+#define BPS_LAUNCH(NT)                                                                                                  \
+    do {                                                                                                                \
+        if (stats)                                                                                                      \
+            hipLaunchKernelGGL((k_raster<NT, true>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,    \
+                               out_depth, out_id, stats, dispatch);                                                     \
+        else                                                                                                            \
+            hipLaunchKernelGGL((k_raster<NT, false>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,   \
+                               out_depth, out_id, stats, dispatch);                                                     \
+    } while (0)
+    if (threads == 256) BPS_LAUNCH(256);
+    else if (threads == 384) BPS_LAUNCH(384);
+    else if (threads == 512) BPS_LAUNCH(512);
+    else BPS_LAUNCH(1024);
+#undef BPS_LAUNCH
 }
 
 }  // namespace bps
