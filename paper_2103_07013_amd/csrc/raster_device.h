@@ -104,7 +104,7 @@ __device__ __forceinline__ void shade_pixel(const Setup& s, int i, int j, bool a
         float num = fmaf(e2, s.iw2, fmaf(e1, s.iw1, e0 * s.iw0));
         float depth = (float)s.A2 / num;
         u64 key = ((u64)__float_as_uint(depth) << 32) | (u64)id;
-        atomicMin(&vis[(j - win.y0) * win.w + (i - win.x0)], key);
+        atomicMin(&vis[__mul24(j - win.y0, win.w) + (i - win.x0)], key);   // 24-bit multiply: full rate
     }
 }
 

@@ -609,7 +609,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                     const uint32_t wbits = (hi32 >> 13) << 12;
                     const int qx = lane & 7, qy = lane >> 3;
                     const bool in = qx <= bw && qy <= bh;
-                    const uint32_t d = in ? vis_hi[2 * ((fy - win.y0 + qy) * win.w + fx - win.x0 + qx)] : 0u;
+                    const uint32_t d = in ? vis_hi[2 * (__mul24(fy - win.y0 + qy, win.w) + fx - win.x0 + qx)] : 0u;
                     if (ballot64(in && d >= wbits) == 0) { ++st_hidden; continue; }
                 }
                 const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
@@ -697,7 +697,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             const int hty = (win.h + 7) >> 3;
             for (int t = wave; t < htx * hty; t += NW) {
                 const int px = ((t % htx) << 3) + (lane & 7), py = ((t / htx) << 3) + (lane >> 3);
-                uint32_t dbits = (px < win.w && py < win.h) ? vis_hi[2 * (py * win.w + px)] : 0u;
+                uint32_t dbits = (px < win.w && py < win.h) ? vis_hi[2 * (__mul24(py, win.w) + px)] : 0u;
 #pragma unroll
                 for (int sh = 32; sh >= 1; sh >>= 1) dbits = max(dbits, (uint32_t)__shfl_xor((int)dbits, sh, 64));
                 if (lane == 0) hiz[t] = dbits;
