@@ -47,7 +47,7 @@ def cpu_baseline(w, n_envs, textured=False):
                             textured=textured and w.rgbd)
     dt = time.perf_counter() - t0
     return dict(value=len(sel) / dt, unit="frames/s", cores=int(r["threads"]), kind="oracle",
-                sample=f"{len(sel)} of {w.B} environments (every {stride}th), same scenes and matrices, {dt:.2f} s wall")
+                sample=f"{len(sel)} of {w.B} environments (stride {stride}), same scenes and matrices, {dt:.2f} s wall")
 
 
 def measured_traffic(key):
@@ -81,9 +81,12 @@ def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=
         bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    launches, kernel_ms = bps.bps_kernel_ms_total(r.handle)
+    each = bps.bps_kernel_ms_each(r.handle)
+    launches, kernel_ms = len(each), float(each.sum())
     bps.bps_set_profiling(r.handle, False)
     res = dict(dt=dt, kernel_ms_avg=kernel_ms / max(launches, 1), launches=launches,
+               kernel_ms_median=float(np.median(each)) if launches else None,
+               kernel_ms_min=float(each.min()) if launches else None,
                clusters=[bps.bps_query(r.handle, h, 0) for h in handles],
                splits=bps.bps_query(r.handle, handles[0], 4), groups=bps.bps_query(r.handle, handles[0], 5),
                threads=bps.bps_query(r.handle, handles[0], 6), lds=bps.bps_query(r.handle, handles[0], 7))
@@ -258,6 +261,21 @@ def main():
                 "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(traffic_key), "kernel": "k_raster",
                 "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes, "accounting": note}
 
+    def copy_ceiling_gbs():
+        """Read + write rate of a plain 1 GiB device-to-device copy: what a pure streaming kernel gets."""
+        n = 1 << 30
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        return 2.0 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     out = {
         "metric": "rendered frames/sec (64x64 depth, 1024 envs) on 1 MI355X",
         "value": w.B * args.steps / dt,
@@ -288,6 +306,12 @@ def main():
     if out["roofline"] is not None:
         out["roofline"].update(extra)
         out["roofline"]["launches_timed"] = main_run["launches"]
+        out["roofline"]["kernel_ms_median"] = main_run["kernel_ms_median"]
+        out["roofline"]["kernel_ms_min"] = main_run["kernel_ms_min"]
+        if not args.no_extras:
+            ceiling = copy_ceiling_gbs()
+            out["roofline"]["copy_ceiling_GBs"] = ceiling
+            out["roofline"]["frac_of_copy_ceiling"] = out["roofline"]["achieved"] / ceiling
     if culling and not args.no_extras:
         steps2 = max(5, args.steps // 5)
         fs = timed_run(bps, torch, w, bps.FLAG_NO_CLUSTER_CULL, steps2, 3, args.splits, args.threads,
@@ -297,6 +321,10 @@ def main():
                       "with cluster culling switched off", f"config{w.number}_full_stream")
         rl["frames_per_s"] = w.B * steps2 / fs["dt"]
         rl["launches_timed"] = fs["launches"]
+        rl["kernel_ms_median"] = fs["kernel_ms_median"]
+        rl["kernel_ms_min"] = fs["kernel_ms_min"]
+        if out["roofline"] is not None and "copy_ceiling_GBs" in out["roofline"]:
+            rl["frac_of_copy_ceiling"] = rl["achieved"] / out["roofline"]["copy_ceiling_GBs"]
         out["roofline_full_stream"] = rl
     if args.rotate and not w.rgbd:
         out["rotation"] = rotation_run(bps, torch, w, max(2000, args.steps), args.warmup)

@@ -145,10 +145,12 @@ bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *
  * bps_last_kernel_ms waits for the most recent request's events and returns its duration in
  * milliseconds.  bps_kernel_ms_total waits for every request profiled since the last call (or
  * since profiling was enabled; at most 4096 are remembered), returns their count and summed
- * duration, and forgets them. */
+ * duration, and forgets them.  bps_kernel_ms_each does the same but writes the individual
+ * durations (at most `capacity`, oldest first) to the host array `out` and their count to *written. */
 bps_status bps_set_profiling(bps_renderer *r, int32_t enable);
 bps_status bps_last_kernel_ms(bps_renderer *r, float *ms);
 bps_status bps_kernel_ms_total(bps_renderer *r, uint32_t *launches, float *total_ms);
+bps_status bps_kernel_ms_each(bps_renderer *r, float *out, uint32_t capacity, uint32_t *written);
 
 /* Diagnostics: when enabled (1), the raster kernel tallies its work into a device block that
  * bps_read_diagnostics copies out after waiting for the device: 16 words per work-group g,

@@ -13,7 +13,7 @@ FLAG_NO_CLUSTER_CULL = 1
 FLAG_NO_OCCLUSION_CULL = 2
 FLAG_NO_DISPATCH_ORDER = 4
 EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_load_scene_textured", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
-           "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
+           "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_kernel_ms_each", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 
 
 class BpsError(RuntimeError):
@@ -63,6 +63,8 @@ def load_library():
     lib.bps_set_profiling.argtypes = [vp, ctypes.c_int32]
     lib.bps_last_kernel_ms.restype = ctypes.c_int32
     lib.bps_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.bps_kernel_ms_each.restype = ctypes.c_int32
+    lib.bps_kernel_ms_each.argtypes = [vp, vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32)]
     lib.bps_kernel_ms_total.restype = ctypes.c_int32
     lib.bps_kernel_ms_total.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_float)]
     lib.bps_set_diagnostics.restype = ctypes.c_int32
@@ -218,6 +220,14 @@ def bps_last_kernel_ms(handle):
     ms = ctypes.c_float(0.0)
     _check(load_library().bps_last_kernel_ms(handle, ctypes.byref(ms)), handle)
     return float(ms.value)
+
+
+def bps_kernel_ms_each(handle, capacity=4096):
+    """Durations (ms) of the requests profiled since the last call, oldest first, as a float32 array."""
+    out = np.zeros(capacity, np.float32)
+    n = ctypes.c_uint32(0)
+    _check(load_library().bps_kernel_ms_each(handle, out.ctypes.data, capacity, ctypes.byref(n)), handle)
+    return out[:int(n.value)].copy()
 
 
 def bps_kernel_ms_total(handle):

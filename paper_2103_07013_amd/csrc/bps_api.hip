@@ -855,6 +855,18 @@ bps_status bps_kernel_ms_total(bps_renderer* r, uint32_t* launches, float* total
     return BPS_OK;
 }
 
+bps_status bps_kernel_ms_each(bps_renderer* r, float* out, uint32_t capacity, uint32_t* written) {
+    if (!r || !out || !written) return BPS_ERR_INVALID_ARG;
+    uint32_t n = 0;
+    for (size_t k = 0; k + 1 < r->ev_used && n < capacity; k += 2, ++n) {
+        BPS_HIP(r, hipEventSynchronize(r->ev[k + 1]));
+        BPS_HIP(r, hipEventElapsedTime(&out[n], r->ev[k], r->ev[k + 1]));
+    }
+    *written = n;
+    r->ev_used = 0;
+    return BPS_OK;
+}
+
 bps_status bps_set_diagnostics(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
     r->want_stats = enable != 0;
