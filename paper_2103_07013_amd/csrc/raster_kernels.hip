@@ -53,8 +53,9 @@ __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u
 __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool want, uint32_t xy0, uint32_t xy1,
                                            uint32_t xy2, float iw0, float iw1, float iw2, uint32_t ref, uint32_t box,
                                            int lane, u64* vis, const Window& win,
-                                           const BPS_GLOBAL uint32_t* ctri_id) {
-    u64 mask = ballot64(want);
+                                           const BPS_GLOBAL uint32_t* ctri_id, u64 mask) {
+    // mask = the lanes that want (handed in: callers build it from ballots of single comparisons,
+    // which cost one compare each, instead of a ballot of the combined condition)
     if (mask == 0) return;
     int n = __popcll(mask);
     L.tally[0] += (uint32_t)n;
@@ -133,17 +134,18 @@ __device__ __forceinline__ bool centre_box(uint32_t xy0, uint32_t xy1, uint32_t 
 __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool valid, short2v lo, short2v ext,
                                      uint32_t xy0, uint32_t xy1, uint32_t xy2, float iw0, float iw1, float iw2,
                                      uint32_t ref, const BPS_GLOBAL uint32_t* ctri_id, int lane, u64* vis,
-                                     const Window& win) {
-    u64 vmask = ballot64(valid);
+                                     const Window& win, u64 vmask) {
+    // vmask = the lanes with valid set
     if (vmask == 0) return;
     int nx = (int)ext.x + 1, ny = (int)ext.y + 1;
     int i_lo = (int)lo.x + 64, j_lo = (int)lo.y + 64;
-    bool small = valid && nx * ny <= kSmallMax;
+    const bool few = nx * ny <= kSmallMax, narrow = nx <= 8, low = ny <= 8;
+    const u64 small_mask = vmask & ballot64(few);
+    const bool small = valid && few;
     uint32_t box = (uint32_t)i_lo | ((uint32_t)j_lo << 8) | ((uint32_t)nx << 16) | ((uint32_t)ny << 24);
-    push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, win, ctri_id);
-    const bool medium = valid && !small && nx <= 8 && ny <= 8;
-    u64 med = ballot64(medium);
-    u64 big = ballot64(valid && !small && !medium);
+    push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, win, ctri_id, small_mask);
+    u64 med = vmask & ~small_mask & ballot64(narrow) & ballot64(low);
+    u64 big = vmask & ~small_mask & ~med;
     L.tally[1] += (uint32_t)__popcll(med | big);
     const uint32_t id = (valid && !small) ? ctri_id[ref] : 0u;
     // medium triangles (box within 8x8 pixels): four per pass, sixteen lanes each, 4x4 pixels per step
@@ -346,19 +348,19 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     const uint32_t tri_ref = c * 128u + slot;
     for (int i = 1; ; ++i) {
         bool v = i + 1 < cnt;
-        if (ballot64(v) == 0) break;
+        const u64 vm = ballot64(v);
+        if (vm == 0) break;
         uint32_t a = v ? pxy[0] : 0u, b = v ? pxy[i] : 0u, d = v ? pxy[i + 1] : 0u;
         float wa = v ? piw[0] : 0.0f, wb = v ? piw[i] : 0.0f, wd = v ? piw[i + 1] : 0.0f;
         short2v lo, ext;
         const bool has = centre_box(a, b, d, win, lo, ext);
-        emit(L, small_count, v && has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, win);
+        emit(L, small_count, v && has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, win, vm & ballot64(has));
     }
 }
 
 // Append straddling triangles to the wave's clip queue (drained by the caller once per cluster,
 // so at most 63 + 128 entries are ever pending).
-__device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool want, uint32_t ref) {
-    u64 mask = ballot64(want);
+__device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool want, uint32_t ref, u64 mask) {
     if (mask == 0) return;
     if (want) L.clipq[count + (int)rank_below(mask)] = ref;
     count += __popcll(mask);
@@ -610,7 +612,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                     const int qx = lane & 7, qy = lane >> 3;
                     const bool in = qx <= bw && qy <= bh;
                     const uint32_t d = in ? vis_hi[2 * (__mul24(fy - win.y0 + qy, win.w) + fx - win.x0 + qx)] : 0u;
-                    if (ballot64(in && d >= wbits) == 0) { ++st_hidden; continue; }
+                    // lanes outside the footprint read d = 0, below every bound (the bound is a positive float)
+                    if (ballot64(d >= wbits) == 0) { ++st_hidden; continue; }
                 }
                 const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
                 nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
@@ -664,22 +667,29 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 const uint32_t i0 = t & 0xFFu, i1 = (t >> 8) & 0xFFu, i2 = t >> 16;
                 float2 a = L.stage[i0], b = L.stage[i1], d = L.stage[i2];
                 bool fast = slot * 64 + lane < ntri;
+                u64 fast_mask = ballot64(fast);      // masks are combined on the scalar unit
                 short2v lo, ext;
                 const bool has = centre_box(__float_as_uint(a.x), __float_as_uint(b.x), __float_as_uint(d.x), win, lo, ext);
+                const u64 has_mask = ballot64(has);
                 if (!all_inside) {
                     uint32_t oa = L.stage_oc[i0], ob = L.stage_oc[i1], od = L.stage_oc[i2];
                     uint32_t o_or = oa | ob | od, o_and = oa & ob & od;
-                    bool live = fast && ((o_or & kInvalid) == 0) && ((o_and & 0x3Fu) == 0);
-                    fast = live && (o_or & 0x3Fu) == 0;
+                    const bool sound = (o_or & kInvalid) == 0, apart = (o_and & 0x3Fu) == 0, crossing = (o_or & 0x3Fu) != 0;
+                    const bool behind = (o_or & kNoProject) != 0;
+                    const bool live = fast && sound && apart;
+                    const u64 live_mask = fast_mask & ballot64(sound) & ballot64(apart), crossing_mask = ballot64(crossing);
+                    fast = live && !crossing;
+                    fast_mask = live_mask & ~crossing_mask;
                     // A straddler whose three vertices all project (w > 0) cannot reach a pixel centre
                     // outside the box of its projected vertices: only the others need the clipper.
-                    const bool straddle = live && (o_or & 0x3Fu) != 0 && (has || (o_or & kNoProject) != 0);
-                    st_straddle += (uint32_t)__popcll(ballot64(straddle));
-                    push_clip(L, clip_count, straddle, (c << 7) | (uint32_t)(slot * 64 + lane));
+                    const bool straddle = live && crossing && (has || behind);
+                    const u64 straddle_mask = live_mask & crossing_mask & (has_mask | ballot64(behind));
+                    st_straddle += (uint32_t)__popcll(straddle_mask);
+                    push_clip(L, clip_count, straddle, (c << 7) | (uint32_t)(slot * 64 + lane), straddle_mask);
                 }
                 emit(L, small_count, fast && has, lo, ext, __float_as_uint(a.x), __float_as_uint(b.x),
                      __float_as_uint(d.x), a.y, b.y, d.y, c * 128u + (uint32_t)(slot * 64 + lane), g_ctri_id, lane, vis,
-                     win);
+                     win, fast_mask & has_mask);
             }
             // ---- clip queue: full wavefronts only while streaming
             while (clip_count >= 64) {
