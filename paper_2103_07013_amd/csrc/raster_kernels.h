@@ -59,7 +59,7 @@ struct FrameParams {
 
 constexpr unsigned long long kEmptyKey = ~0ull;
 constexpr int kOrigin = 16384;         // packed screen coordinates are stored relative to pixel 64
-constexpr int kSmallMax = 4;           // pixel centres a "small" triangle may touch
+constexpr int kSmallMax = 9;           // pixel centres a "small" triangle may touch (one lane rasterises it)
 constexpr uint32_t kInvalid = 0x40u;   // outcode bit: vertex unusable, drop its triangles
 constexpr uint32_t kNoProject = 0x80u; // outcode bit: vertex has no finite screen position (w <= 0 or overflow)
 
