@@ -38,14 +38,34 @@ __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u
     Setup s = make_setup(xy0, xy1, xy2, iw0, iw1, iw2);
     int i_lo = (int)(box & 0xFFu), j_lo = (int)((box >> 8) & 0xFFu);
     int nx = (int)((box >> 16) & 0xFFu), ny = (int)(box >> 24);
-    int cnt = have ? nx * ny : 0;
-    int i = i_lo, j = j_lo;
+    int cnt = (have && s.A2 != 0) ? nx * ny : 0;
+    // Edge functions at the first pixel centre, then stepped: one pixel to the right changes edge k by
+    // -256 dy_k, and going from the end of a row to the start of the next by 256 dx_k + 256 (nx - 1) dy_k.
+    // Same integers as evaluating each pixel afresh (all of them are areas inside the triangle's box).
+    const int px = (i_lo << 8) + 128 - kOrigin, py = (j_lo << 8) + 128 - kOrigin;
+    int E0 = __mul24(s.dx0, py - s.Y1) - __mul24(s.dy0, px - s.X1);
+    int E1 = __mul24(s.dx1, py - s.Y2) - __mul24(s.dy1, px - s.X2);
+    int E2 = __mul24(s.dx2, py - s.Y0) - __mul24(s.dy2, px - s.X0);
+    const int right0 = -(s.dy0 << 8), right1 = -(s.dy1 << 8), right2 = -(s.dy2 << 8);
+    const int wrap0 = (s.dx0 + __mul24(nx - 1, s.dy0)) << 8, wrap1 = (s.dx1 + __mul24(nx - 1, s.dy1)) << 8,
+              wrap2 = (s.dx2 + __mul24(nx - 1, s.dy2)) << 8;
+    int at = __mul24(j_lo - win.y0, win.w) + (i_lo - win.x0), col = 0;
+    const int at_wrap = win.w - nx + 1;
+    const float a2f = (float)s.A2;
     for (int k = 0; k < kSmallMax; ++k) {
-        bool act = k < cnt;
+        const bool act = k < cnt;
         if (ballot64(act) == 0) break;
-        shade_pixel(s, i, j, act, id, vis, win);
-        ++i;
-        if (i >= i_lo + nx) { i = i_lo; ++j; }
+        if (act && (((E0 + s.b0) | (E1 + s.b1) | (E2 + s.b2)) >= 0)) {
+            const float num = fmaf((float)E2, s.iw2, fmaf((float)E1, s.iw1, (float)E0 * s.iw0));
+            const float depth = a2f / num;
+            atomicMin(&vis[at], ((u64)__float_as_uint(depth) << 32) | (u64)id);
+        }
+        const bool row_end = ++col == nx;
+        E0 += row_end ? wrap0 : right0;
+        E1 += row_end ? wrap1 : right1;
+        E2 += row_end ? wrap2 : right2;
+        at += row_end ? at_wrap : 1;
+        col = row_end ? 0 : col;
     }
 }
 
