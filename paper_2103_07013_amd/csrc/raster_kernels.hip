@@ -389,7 +389,7 @@ __device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool wan
 }  // namespace
 
 // =============================================================================================
-template <int NT, bool DIAG>
+template <int NT, bool DIAG, int CULL>
 __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
@@ -469,14 +469,16 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     const uint32_t nblocks_total = (sc.n_clusters + 63u) / 64u;
     const uint32_t nb_item = nblocks_total > item_split ? (nblocks_total - item_split + S - 1u) / S : 0u;
     const BPS_GLOBAL float* g_bbounds = gptr(sc.bbounds);
-    const bool occlusion = fp.cull > 1;
+    // CULL is the culling level the instance is compiled for: 0 none (every cluster of the scene is
+    // streamed), 1 frustum tests only, 2 frustum and occlusion tests (the default)
+    constexpr bool occlusion = CULL > 1;
     const uint32_t* vis_hi = reinterpret_cast<const uint32_t*>(vis) + 1;   // depth word of pixel p is vis_hi[2 p]
 
     // ---- prologue: counters, and the item's blocks ordered near to far
     if (tid < 8) counters[tid] = 0u;
     for (int t = tid; t < kHizTiles; t += NT) hiz[t] = 0xFFFFFFFFu;   // nothing drawn yet: no tile hides anything
     __syncthreads();
-    const bool sorted = fp.cull != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)fp.list_cap && nb_item > 1;
+    const bool sorted = CULL != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)fp.list_cap && nb_item > 1;
     if (sorted) {
         // key: smallest clip w over the block's bounding box (exactly attained at a corner), as a
         // sortable integer so that any bit pattern, NaN included, has a unique rank
@@ -551,7 +553,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             bool visible = cl < sc.n_clusters;
             uint32_t foot = 0u, wb19 = 0u;
             st_tested += (uint32_t)__popcll(ballot64(visible));
-            if (fp.cull) {
+            if (CULL != 0) {
                 const uint32_t cc = visible ? cl : 0u;
                 float lx = g_bounds[cc], ly = g_bounds[sc.c_stride + cc], lz = g_bounds[2 * sc.c_stride + cc];
                 float hx = g_bounds[3 * sc.c_stride + cc], hy = g_bounds[4 * sc.c_stride + cc],
@@ -966,38 +968,49 @@ __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n) {
 }
 
 namespace {
-template <bool DIAG>
+template <bool DIAG, int CULL>
 const void* raster_entry(int threads) {
-    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG>)
-           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG>)
-           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG>)
-                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG>);
+    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG, CULL>)
+           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG, CULL>)
+           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG, CULL>)
+                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG, CULL>);
 }
 }  // namespace
 
 hipError_t prepare_raster(int threads, size_t lds) {
-    hipError_t e = hipFuncSetAttribute(raster_entry<false>(threads), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(raster_entry<true>(threads), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const void* entries[6] = {raster_entry<false, 0>(threads), raster_entry<false, 1>(threads), raster_entry<false, 2>(threads),
+                              raster_entry<true, 0>(threads),  raster_entry<true, 1>(threads),  raster_entry<true, 2>(threads)};
+    for (const void* f : entries) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch) {
-#define BPS_LAUNCH(NT)                                                                                                  \
-    do {                                                                                                                \
-        if (stats)                                                                                                      \
-            hipLaunchKernelGGL((k_raster<NT, true>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,    \
-                               out_depth, out_id, stats, dispatch);                                                     \
-        else                                                                                                            \
-            hipLaunchKernelGGL((k_raster<NT, false>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,   \
-                               out_depth, out_id, stats, dispatch);                                                     \
+#define BPS_LAUNCH3(NT, DIAG, CULL)                                                                                    \
+    hipLaunchKernelGGL((k_raster<NT, DIAG, CULL>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,      \
+                       out_depth, out_id, stats, dispatch)
+#define BPS_LAUNCH2(NT, DIAG)                                                                                          \
+    do {                                                                                                               \
+        if (fp.cull == 0) BPS_LAUNCH3(NT, DIAG, 0);                                                                    \
+        else if (fp.cull == 1) BPS_LAUNCH3(NT, DIAG, 1);                                                               \
+        else BPS_LAUNCH3(NT, DIAG, 2);                                                                                 \
+    } while (0)
+#define BPS_LAUNCH(NT)                                                                                                 \
+    do {                                                                                                               \
+        if (stats) BPS_LAUNCH2(NT, true);                                                                              \
+        else BPS_LAUNCH2(NT, false);                                                                                   \
     } while (0)
     if (threads == 256) BPS_LAUNCH(256);
     else if (threads == 384) BPS_LAUNCH(384);
     else if (threads == 512) BPS_LAUNCH(512);
     else BPS_LAUNCH(1024);
 #undef BPS_LAUNCH
+#undef BPS_LAUNCH2
+#undef BPS_LAUNCH3
 }
 
 }  // namespace bps
