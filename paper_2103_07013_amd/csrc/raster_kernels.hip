@@ -389,7 +389,7 @@ __device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool wan
 }  // namespace
 
 // =============================================================================================
-template <int NT, bool DIAG, int CULL>
+template <int NT, bool DIAG, int CULL, bool WHOLE64>
 __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
@@ -439,14 +439,21 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     // this work-group's window of the frame
     const int tiles_x = (fp.W + fp.tile_w - 1) / fp.tile_w;
     Window win;
-    win.x0 = (int)(item.tile % (uint32_t)tiles_x) * fp.tile_w;
-    win.y0 = (int)(item.tile / (uint32_t)tiles_x) * fp.tile_h;
-    win.w = min(fp.tile_w, fp.W - win.x0);
-    win.h = min(fp.tile_h, fp.H - win.y0);
-    win.aL = 2.0f * (float)win.x0 / (float)fp.W - 1.0f;
-    win.aR = 2.0f * (float)(win.x0 + win.w) / (float)fp.W - 1.0f;
-    win.aT = 2.0f * (float)win.y0 / (float)fp.H - 1.0f;
-    win.aB = 2.0f * (float)(win.y0 + win.h) / (float)fp.H - 1.0f;
+    if (WHOLE64) {
+        // the instance for 64x64 frames (the paper's main resolution): the window is the frame, and
+        // with its origin and size known to the compiler the pixel arithmetic of every loop shrinks
+        win.x0 = 0; win.y0 = 0; win.w = 64; win.h = 64;
+        win.aL = -1.0f; win.aR = 1.0f; win.aT = -1.0f; win.aB = 1.0f;
+    } else {
+        win.x0 = (int)(item.tile % (uint32_t)tiles_x) * fp.tile_w;
+        win.y0 = (int)(item.tile / (uint32_t)tiles_x) * fp.tile_h;
+        win.w = min(fp.tile_w, fp.W - win.x0);
+        win.h = min(fp.tile_h, fp.H - win.y0);
+        win.aL = 2.0f * (float)win.x0 / (float)fp.W - 1.0f;
+        win.aR = 2.0f * (float)(win.x0 + win.w) / (float)fp.W - 1.0f;
+        win.aT = 2.0f * (float)win.y0 / (float)fp.H - 1.0f;
+        win.aB = 2.0f * (float)(win.y0 + win.h) / (float)fp.H - 1.0f;
+    }
     const int npix = win.w * win.h;
     for (int p = tid; p < npix; p += NT) vis[p] = kEmptyKey;
 
@@ -970,10 +977,10 @@ __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n) {
 namespace {
 template <bool DIAG, int CULL>
 const void* raster_entry(int threads) {
-    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG, CULL>)
-           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG, CULL>)
-           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG, CULL>)
-                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG, CULL>);
+    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG, CULL, false>)
+           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG, CULL, false>)
+           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG, CULL, false>)
+                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG, CULL, false>);
 }
 }  // namespace
 
@@ -984,14 +991,21 @@ hipError_t prepare_raster(int threads, size_t lds) {
         hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_raster<512, false, 2, true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch) {
+    // 64x64 frames in the default configuration have an instance of their own
+    if (threads == 512 && !stats && fp.cull == 2 && fp.W == 64 && fp.H == 64 && fp.tile_w == 64 && fp.tile_h == 64) {
+        hipLaunchKernelGGL((k_raster<512, false, 2, true>), grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis,
+                           out_depth, out_id, stats, dispatch);
+        return;
+    }
 #define BPS_LAUNCH3(NT, DIAG, CULL)                                                                                    \
-    hipLaunchKernelGGL((k_raster<NT, DIAG, CULL>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,      \
+    hipLaunchKernelGGL((k_raster<NT, DIAG, CULL, false>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,      \
                        out_depth, out_id, stats, dispatch)
 #define BPS_LAUNCH2(NT, DIAG)                                                                                          \
     do {                                                                                                               \
