@@ -65,6 +65,7 @@ constexpr uint32_t kNoProject = 0x80u; // outcode bit: vertex has no finite scre
 
 // per-wave LDS block: 64 staged vertices (8 B + 4 B outcode each), small queue 8 x 64 words,
 // clip queue 192 words
+constexpr uint32_t kListCap64 = 1408;   // survivor-list capacity of the 64x64 instance (two groups per compute unit)
 constexpr uint32_t kWaveLdsBytes = 64 * 12 + 8 * 64 * 4 + 192 * 4;
 
 constexpr int kOrderCap = 1024;        // blocks of one item that can be depth-sorted

@@ -404,7 +404,10 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int HW = fp.tile_w * fp.tile_h;      // LDS is sized for a full tile; edge tiles may be smaller
+    // LDS is sized for a full tile; edge tiles may be smaller.  The 64x64 instance also fixes the
+    // capacity of the survivor list, so that every LDS address below is a compile-time constant.
+    const int HW = WHOLE64 ? 64 * 64 : fp.tile_w * fp.tile_h;
+    const int list_cap = WHOLE64 ? (int)kListCap64 : fp.list_cap;
 
     u64* vis = reinterpret_cast<u64*>(smem);
     unsigned char* wbase = smem + (size_t)HW * 8 + (size_t)wave * kWaveLdsBytes;
@@ -418,10 +421,10 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 
     unsigned char* shared = smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes;
     u64* list = reinterpret_cast<u64*>(shared);                                 // [list_cap] surviving clusters
-    uint16_t* order = reinterpret_cast<uint16_t*>(shared + (size_t)fp.list_cap * 8);   // [kOrderCap] blocks, near to far
-    uint16_t* perm = reinterpret_cast<uint16_t*>(shared + (size_t)fp.list_cap * 8 + kOrderCap * 2);   // [list_cap] pop order
-    uint16_t* slot_in_bin = perm + fp.list_cap;                                                       // [list_cap]
-    uint32_t* hist = reinterpret_cast<uint32_t*>(slot_in_bin + fp.list_cap);                          // [2][kDepthBins]
+    uint16_t* order = reinterpret_cast<uint16_t*>(shared + (size_t)list_cap * 8);   // [kOrderCap] blocks, near to far
+    uint16_t* perm = reinterpret_cast<uint16_t*>(shared + (size_t)list_cap * 8 + kOrderCap * 2);   // [list_cap] pop order
+    uint16_t* slot_in_bin = perm + list_cap;                                                       // [list_cap]
+    uint32_t* hist = reinterpret_cast<uint32_t*>(slot_in_bin + list_cap);                          // [2][kDepthBins]
     uint32_t* hiz = hist + 2 * kDepthBins;                                                            // [kHizTiles]
     uint32_t* counters = hiz + kHizTiles;
     uint32_t* list_count = counters;       // survivors appended in this round
@@ -485,7 +488,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     if (tid < 8) counters[tid] = 0u;
     for (int t = tid; t < kHizTiles; t += NT) hiz[t] = 0xFFFFFFFFu;   // nothing drawn yet: no tile hides anything
     __syncthreads();
-    const bool sorted = CULL != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)fp.list_cap && nb_item > 1;
+    const bool sorted = CULL != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)list_cap && nb_item > 1;
     if (sorted) {
         // key: smallest clip w over the block's bounding box (exactly attained at a corner), as a
         // sortable integer so that any bit pattern, NaN included, has a unique rank
@@ -545,7 +548,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             uint32_t r0 = 0, blk = 0;
             if (lane == 0) r0 = atomicAdd(reserved, 64u);
             r0 = __builtin_amdgcn_readfirstlane(r0);
-            if (r0 + 64u > (uint32_t)fp.list_cap) {
+            if (r0 + 64u > (uint32_t)list_cap) {
                 if (lane == 0) atomicSub(reserved, 64u);
                 break;
             }
@@ -999,7 +1002,8 @@ void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch) {
     // 64x64 frames in the default configuration have an instance of their own
-    if (threads == 512 && !stats && fp.cull == 2 && fp.W == 64 && fp.H == 64 && fp.tile_w == 64 && fp.tile_h == 64) {
+    if (threads == 512 && !stats && fp.cull == 2 && fp.W == 64 && fp.H == 64 && fp.tile_w == 64 && fp.tile_h == 64 &&
+        fp.list_cap == (int)kListCap64) {
         hipLaunchKernelGGL((k_raster<512, false, 2, true>), grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis,
                            out_depth, out_id, stats, dispatch);
         return;
