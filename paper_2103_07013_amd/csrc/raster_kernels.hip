@@ -406,6 +406,11 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // LDS is sized for a full tile; edge tiles may be smaller.  The 64x64 instance also fixes the
     // capacity of the survivor list, so that every LDS address below is a compile-time constant.
+    FrameParams fq = fp;      // the frame parameters the loops use: constants in the 64x64 instance
+    if (WHOLE64) {
+        fq.H = 64; fq.W = 64; fq.tile_w = 64; fq.tile_h = 64;
+        fq.sx = 8192.0f; fq.sy = 8192.0f; fq.xmax = 16448.0f; fq.ymax = 16448.0f;
+    }
     const int HW = WHOLE64 ? 64 * 64 : fp.tile_w * fp.tile_h;
     const int list_cap = WHOLE64 ? (int)kListCap64 : fp.list_cap;
 
@@ -570,7 +575,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                       hz = g_bounds[5 * sc.c_stride + cc];
                 visible = visible && !box_outside_frustum(M, win, lx, ly, lz, hx, hy, hz);
                 if (occlusion && visible) {
-                    foot = box_footprint(M, fp, win, lx, ly, lz, hx, hy, hz, wb19);
+                    foot = box_footprint(M, fq, win, lx, ly, lz, hx, hy, hz, wb19);
                     visible = foot != kNoPixel;
                     if (visible && (foot & 1u)) {
                         // coarse test against the largest depth per 8x8 tile as of the end of the last round
@@ -698,7 +703,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             uint32_t xy;
             float iw;
             bool can_project;
-            bool ok = project(cp, fp, xy, iw, can_project);
+            bool ok = project(cp, fq, xy, iw, can_project);
             if (oc == 0 && !ok) oc = kInvalid;
             if (!can_project) oc |= kNoProject;
             const bool all_inside = ballot64(oc != 0) == 0;
@@ -748,7 +753,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             // ---- clip queue: full wavefronts only while streaming
             while (clip_count >= 64) {
                 wave_lds_sync();
-                drain_clip(L, clip_count - 64, 64, small_count, sc, M, fp, win, lane, vis);
+                drain_clip(L, clip_count - 64, 64, small_count, sc, M, fq, win, lane, vis);
                 clip_count -= 64;
             }
         }
@@ -774,7 +779,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     }
     if (clip_count > 0) {
         wave_lds_sync();
-        drain_clip(L, 0, clip_count, small_count, sc, M, fp, win, lane, vis);
+        drain_clip(L, 0, clip_count, small_count, sc, M, fq, win, lane, vis);
     }
     if (small_count > 0) {
         wave_lds_sync();
@@ -812,10 +817,10 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     }
 
     // ---- resolve this work-group's frame
-    const size_t base = (size_t)item.env * fp.H * fp.W;
+    const size_t base = (size_t)item.env * fq.H * fq.W;
     for (int p = tid; p < npix; p += NT) {
         const int y = p / win.w, x = p - y * win.w;
-        const size_t o = base + (size_t)(win.y0 + y) * fp.W + (size_t)(win.x0 + x);
+        const size_t o = base + (size_t)(win.y0 + y) * fq.W + (size_t)(win.x0 + x);
         const u64 key = vis[p];
         const bool hit = key != kEmptyKey;
         if (fp.merge) {
