@@ -257,14 +257,15 @@ constexpr uint32_t kNoPixel = 0xFFFFFFFFu;   // box_footprint: the box cannot co
 // box.  So if the smallest w over the box (minus a rounding margin) is larger than the depth
 // already stored at every pixel whose centre the projected box can reach, nothing in the box can
 // win the z-test.  Returns the packed test record, or 0 when no bound can be given (the box
-// may reach the eye plane, or is more than 8 pixels wide or high):
-//   bit 0 testable | x0 7 bits | y0 7 bits | width-1 3 bits | height-1 3 bits | top 19 bits of the
-//   w bound (truncated, i.e. rounded towards the eye)
+// may reach the eye plane, or is more than 32 pixels wide or high):
+//   bit 0 testable | x0 6 bits | y0 6 bits (both relative to the window) | width-1 5 bits |
+//   height-1 5 bits, and in wbits18 the exponent and top ten mantissa bits of the w bound
+//   (truncated, i.e. rounded towards the eye)
 __device__ __forceinline__ uint32_t box_footprint(const float (&M)[16], const FrameParams& fp, const Window& win,
                                                  float lx, float ly, float lz, float hx, float hy, float hz,
-                                                 uint32_t& wbits19) {
+                                                 uint32_t& wbits18) {
     const float eps = 1.52587890625e-05f;   // 2^-16
-    wbits19 = 0u;
+    wbits18 = 0u;
     float ax = fmaxf(fabsf(lx), fabsf(hx)), ay = fmaxf(fabsf(ly), fabsf(hy)), az = fmaxf(fabsf(lz), fabsf(hz));
     float wmin = M[15] + fminf(M[12] * lx, M[12] * hx) + fminf(M[13] * ly, M[13] * hy) + fminf(M[14] * lz, M[14] * hz);
     float wmag = fmaf(fabsf(M[12]), ax, fmaf(fabsf(M[13]), ay, fmaf(fabsf(M[14]), az, fabsf(M[15]))));
@@ -293,16 +294,16 @@ __device__ __forceinline__ uint32_t box_footprint(const float (&M)[16], const Fr
     if (fx0 > fx1 || fy0 > fy1) return kNoPixel;
     int ix0 = (int)fx0, ix1 = (int)fx1, iy0 = (int)fy0, iy1 = (int)fy1;
     int bw = ix1 - ix0, bh = iy1 - iy0;
-    if (bw > 7 || bh > 7) return 0u;
-    wbits19 = __float_as_uint(wcons) >> 12;
-    return 1u | ((uint32_t)ix0 << 1) | ((uint32_t)iy0 << 8) | ((uint32_t)bw << 15) | ((uint32_t)bh << 18);
+    if (bw > 31 || bh > 31) return 0u;
+    wbits18 = __float_as_uint(wcons) >> 13;      // positive: the sign bit is clear, 18 bits remain
+    return 1u | ((uint32_t)(ix0 - win.x0) << 1) | ((uint32_t)(iy0 - win.y0) << 7) | ((uint32_t)bw << 13) | ((uint32_t)bh << 18);
 }
 
 // Depth bin of a survivor record: exponent and top three mantissa bits of its w bound, i.e.
 // eight bins per octave from 2^-7 upwards; records without a bound (near or large boxes) go first.
 __device__ __forceinline__ int depth_bin(u64 e) {
-    if (!((e >> 24) & 1ull)) return 0;
-    int k = (int)(e >> 53) - 120 * 8;     // wbits19 >> 8
+    if (!((e >> 23) & 1ull)) return 0;
+    int k = (int)(e >> 53) - 120 * 8;     // exponent and three mantissa bits of the w bound
     return min(max(k, 0), kDepthBins - 1);
 }
 
@@ -566,7 +567,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             const uint32_t jb = sorted ? (uint32_t)order[blk] : blk;
             const uint32_t cl = (jb * S + item_split) * 64u + (uint32_t)lane;
             bool visible = cl < sc.n_clusters;
-            uint32_t foot = 0u, wb19 = 0u;
+            uint32_t foot = 0u, wb18 = 0u;
             st_tested += (uint32_t)__popcll(ballot64(visible));
             if (CULL != 0) {
                 const uint32_t cc = visible ? cl : 0u;
@@ -575,24 +576,26 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                       hz = g_bounds[5 * sc.c_stride + cc];
                 visible = visible && !box_outside_frustum(M, win, lx, ly, lz, hx, hy, hz);
                 if (occlusion && visible) {
-                    foot = box_footprint(M, fq, win, lx, ly, lz, hx, hy, hz, wb19);
+                    foot = box_footprint(M, fq, win, lx, ly, lz, hx, hy, hz, wb18);
                     visible = foot != kNoPixel;
                     if (visible && (foot & 1u)) {
                         // coarse test against the largest depth per 8x8 tile as of the end of the last round
-                        const int fx = (int)((foot >> 1) & 127u) - win.x0, fy = (int)((foot >> 8) & 127u) - win.y0;
-                        const int tx0 = fx >> 3, tx1 = (fx + (int)((foot >> 15) & 7u)) >> 3;
-                        const int ty0 = fy >> 3, ty1 = (fy + (int)((foot >> 18) & 7u)) >> 3;
-                        uint32_t zmax = max(max(hiz[ty0 * htx + tx0], hiz[ty0 * htx + tx1]),
-                                            max(hiz[ty1 * htx + tx0], hiz[ty1 * htx + tx1]));
-                        if ((wb19 << 12) > zmax) visible = false;
+                        const int fx = (int)((foot >> 1) & 63u), fy = (int)((foot >> 7) & 63u);     // window-relative
+                        const int bw = (int)((foot >> 13) & 31u), bh = (int)((foot >> 18) & 31u);
+                        if (bw <= 7 && bh <= 7) {     // at most 2 x 2 tiles: their corners are all of them
+                            const int tx0 = fx >> 3, tx1 = (fx + bw) >> 3;
+                            const int ty0 = fy >> 3, ty1 = (fy + bh) >> 3;
+                            uint32_t zmax = max(max(hiz[ty0 * htx + tx0], hiz[ty0 * htx + tx1]),
+                                                max(hiz[ty1 * htx + tx0], hiz[ty1 * htx + tx1]));
+                            if ((wb18 << 13) > zmax) visible = false;
+                        }
                         // Footprints of at most 4x4 pixels are then checked pixel by pixel, all 64 clusters
                         // at once (no wavefront is drawing during this phase): the same test a wavefront
                         // would make alone when it pops the cluster, at a fortieth of the cost.
-                        const int bw = (int)((foot >> 15) & 7u), bh = (int)((foot >> 18) & 7u);
                         const bool fine = visible && later_round && bw <= 3 && bh <= 3;
                         if (ballot64(fine) != 0ull) {
                             const int n = fine ? (bw + 1) * (bh + 1) : 0;
-                            const uint32_t bound = wb19 << 12;
+                            const uint32_t bound = wb18 << 13;
                             int at = __mul24(fy, win.w) + fx, col = 0;
                             bool seen = false;
                             for (int k = 0; k < 16; ++k) {
@@ -618,7 +621,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 atomicSub(reserved, 64u - n_keep);
             }
             base = __builtin_amdgcn_readfirstlane(base);
-            if (visible) list[base + rank_below(keep)] = (u64)cl | ((u64)foot << 24) | ((u64)wb19 << 45);
+            // record: cluster 23 bits | footprint 23 bits | w bound 18 bits
+            if (visible) list[base + rank_below(keep)] = (u64)cl | ((u64)foot << 23) | ((u64)wb18 << 46);
         }
         TICK(1);
         __syncthreads();
@@ -662,17 +666,25 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 const u64 e = list[by_depth ? (uint32_t)perm[pop] : pop];
                 const uint32_t lo32 = __builtin_amdgcn_readfirstlane((uint32_t)e);
                 const uint32_t hi32 = __builtin_amdgcn_readfirstlane((uint32_t)(e >> 32));
-                c_next = lo32 & 0x00FFFFFFu;
-                const uint32_t foot = (lo32 >> 24) | (hi32 << 8);
+                c_next = lo32 & 0x007FFFFFu;
+                const uint32_t foot = (lo32 >> 23) | (hi32 << 9);
                 if (foot & 1u) {
-                    const int fx = (int)((foot >> 1) & 127u), fy = (int)((foot >> 8) & 127u);
-                    const int bw = (int)((foot >> 15) & 7u), bh = (int)((foot >> 18) & 7u);
-                    const uint32_t wbits = (hi32 >> 13) << 12;
-                    const int qx = lane & 7, qy = lane >> 3;
-                    const bool in = qx <= bw && qy <= bh;
-                    const uint32_t d = in ? vis_hi[2 * (__mul24(fy - win.y0 + qy, win.w) + fx - win.x0 + qx)] : 0u;
-                    // lanes outside the footprint read d = 0, below every bound (the bound is a positive float)
-                    if (ballot64(d >= wbits) == 0) { ++st_hidden; continue; }
+                    const int fx = (int)((foot >> 1) & 63u), fy = (int)((foot >> 7) & 63u);
+                    const int bw = (int)((foot >> 13) & 31u), bh = (int)((foot >> 18) & 31u);
+                    const uint32_t wbits = (hi32 >> 14) << 13;
+                    // the wavefront covers the footprint in passes of 64 pixels: rows of 1, 2, 4, ... 32
+                    // pixels (the smallest power of two that holds the width), as many rows as fit
+                    const int cols_log2 = bw == 0 ? 0 : 32 - __builtin_clz((uint32_t)bw);
+                    const int qx = lane & ((1 << cols_log2) - 1), qy = lane >> cols_log2;
+                    const int rows_per_pass = 64 >> cols_log2;
+                    bool shows = false;
+                    for (int row0 = 0; row0 <= bh && !shows; row0 += rows_per_pass) {
+                        const bool in = qx <= bw && row0 + qy <= bh;
+                        const uint32_t d = in ? vis_hi[2 * (__mul24(fy + row0 + qy, win.w) + fx + qx)] : 0u;
+                        // lanes outside the footprint read d = 0, below every bound (the bound is a positive float)
+                        shows = ballot64(d >= wbits) != 0ull;
+                    }
+                    if (!shows) { ++st_hidden; continue; }
                 }
                 const BPS_GLOBAL float* cv = g_cverts + (size_t)c_next * 192;
                 nx_ = cv[lane]; ny_ = cv[64 + lane]; nz_ = cv[128 + lane];
