@@ -922,15 +922,20 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
     __syncthreads();
     // exclusive prefix sum over the buckets: two per thread, then a scan over the 1024 pair sums
     const uint32_t a0 = bucket[2 * tid], a1 = bucket[2 * tid + 1];
-    scan[tid] = a0 + a1;
-    __syncthreads();
-    for (uint32_t step = 1; step < 1024u; step <<= 1) {
-        const uint32_t v = tid >= step ? scan[tid - step] : 0u;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
+    // inclusive scan of the 1024 pair sums: within each wavefront by shuffles, then over the 16
+    // wavefront totals
+    uint32_t incl = a0 + a1;
+#pragma unroll
+    for (int step = 1; step < 64; step <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, step, 64);
+        if ((tid & 63u) >= (uint32_t)step) incl += up;
     }
-    const uint32_t before = scan[tid] - (a0 + a1);
+    if ((tid & 63u) == 63u) scan[tid >> 6] = incl;
+    __syncthreads();
+    uint32_t offset = 0;
+    for (uint32_t wv = 0; wv < (tid >> 6); ++wv) offset += scan[wv];
+    const uint32_t before = offset + incl - (a0 + a1);
+    __syncthreads();       // scan[] is reused below
     bucket[2 * tid] = before;
     bucket[2 * tid + 1] = before + a0;
     __syncthreads();
