@@ -471,11 +471,9 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0, st_hidden = 0, st_hiz = 0;
     const unsigned long long t_start = stats ? wall_clock64() : 0ull;
     // phase timers (diagnostics only): ticks[k] accumulates the time since the previous TICK
-    unsigned long long t_prev = t_start, t_c0 = 0;
+    unsigned long long t_prev = t_start;
     uint32_t ticks[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #define TICK(k) do { if (phase_timers) { unsigned long long t_ = wall_clock64(); ticks[k] += (uint32_t)(t_ - t_prev); t_prev = t_; } } while (0)
-#define TICKC0() do { if (stats) t_c0 = wall_clock64(); } while (0)
-#define TICKC(k) do { if (stats) ticks[k] += (uint32_t)(wall_clock64() - t_c0); } while (0)
     const uint32_t full_tri_mask = 0x00FFFFFFu;
     const BPS_GLOBAL float* g_cverts = gptr(sc.cverts);
     const BPS_GLOBAL uint32_t* g_ctris = gptr(sc.ctris);
