@@ -1,7 +1,6 @@
-// Cluster builder: order triangles along a Morton curve through their centroids so that
-// neighbours in the list are neighbours in space, then cut the list greedily whenever the
-// next triangle would not fit (more than 64 distinct vertices or more than 128 triangles).
-// A short look-ahead window prefers triangles that reuse vertices already in the cluster.
+// Cluster builder: triangles are ordered along a Morton curve through their centroids; clusters
+// are seeded in that order and grown over the mesh's vertex adjacency into compact patches of at
+// most 64 distinct vertices and 128 triangles.
 #include "clusters.h"
 
 #include <algorithm>
@@ -51,73 +50,132 @@ ClusterSet build_clusters(const float* vertices, uint32_t V, const uint32_t* ind
     }
     std::sort(keyed.begin(), keyed.end());
 
-    // ---- greedy cut with look-ahead
-    std::vector<uint32_t> stamp(V, 0xFFFFFFFFu);  // cluster that last used the vertex
+    // ---- region growing
+    // A cluster starts at the first unassigned triangle of the spatial order and grows by the
+    // triangle that costs least: fewest vertices not yet in the cluster first, then least growth of
+    // the cluster's bounding box (compact clusters have small screen footprints, which is what the
+    // renderer's culling tests look at).  Candidates are the unassigned triangles that touch a
+    // vertex of the cluster; where the mesh offers none (unconnected triangles) the next ones in
+    // spatial order stand in.
+    std::vector<uint32_t> vstart(V + 1, 0);
+    for (size_t i = 0; i < (size_t)T * 3; ++i) ++vstart[indices[i] + 1];
+    for (uint32_t v = 0; v < V; ++v) vstart[v + 1] += vstart[v];
+    std::vector<uint32_t> vtris((size_t)T * 3);
+    {
+        std::vector<uint32_t> fill(vstart.begin(), vstart.end() - 1);
+        for (uint32_t tt = 0; tt < T; ++tt)
+            for (int k = 0; k < 3; ++k) vtris[fill[indices[3 * (size_t)tt + k]]++] = tt;
+    }
+    std::vector<uint32_t> stamp(V, 0xFFFFFFFFu);     // cluster that last used the vertex
     std::vector<uint8_t> local(V, 0);
-    std::vector<uint8_t> taken(T, 0);             // position in `keyed` already assigned
+    std::vector<uint8_t> taken(T, 0);                // by triangle
+    std::vector<uint32_t> listed(T, 0xFFFFFFFFu);    // cluster whose candidate list holds the triangle
+    std::vector<uint32_t> cand;
     out.verts.reserve((size_t)(T / 90 + 1) * 192);
     out.tris.reserve((size_t)(T / 90 + 1) * 128);
     out.tri_id.reserve((size_t)(T / 90 + 1) * 128);
 
-    uint32_t head = 0;  // first position not yet assigned
-    while (head < T) {
-        uint32_t c = out.count++;
+    uint32_t head = 0;  // first position of the spatial order not yet assigned
+    while (true) {
+        while (head < T && taken[(uint32_t)keyed[head]]) ++head;
+        if (head >= T) break;
+        const uint32_t c = out.count++;
         size_t vbase = out.verts.size(), tbase = out.tris.size();
         out.verts.resize(vbase + 192, 0.0f);
         out.tris.resize(tbase + 128, 0u);
         out.tri_id.resize(tbase + 128, 0xFFFFFFFFu);
         uint32_t nv = 0, nt = 0;
         float bl[3] = {INFINITY, INFINITY, INFINITY}, bh[3] = {-INFINITY, -INFINITY, -INFINITY};
-        while (nt < kClusterTris) {
-            while (head < T && taken[head]) ++head;
-            if (head >= T) break;
-            // pick, among the next kWindow unassigned triangles, the one adding fewest vertices
-            uint32_t best = 0xFFFFFFFFu, best_new = 4, seen = 0;
-            for (uint32_t p = head; p < T && seen < kWindow; ++p) {
-                if (taken[p]) continue;
-                ++seen;
-                uint32_t t = (uint32_t)keyed[p];
-                uint32_t fresh = 0;
-                for (int k = 0; k < 3; ++k) fresh += stamp[indices[3 * (size_t)t + k]] != c;
-                // repeated index inside one triangle counts once
-                const uint32_t* ix = indices + 3 * (size_t)t;
-                if (fresh > 1 && (ix[0] == ix[1] || ix[1] == ix[2] || ix[0] == ix[2])) {
-                    uint32_t d = 0;
-                    if (stamp[ix[0]] != c) ++d;
-                    if (ix[1] != ix[0] && stamp[ix[1]] != c) ++d;
-                    if (ix[2] != ix[0] && ix[2] != ix[1] && stamp[ix[2]] != c) ++d;
-                    fresh = d;
-                }
-                if (fresh < best_new) {
-                    best_new = fresh;
-                    best = p;
-                    if (fresh == 0) break;
-                }
-                // the head triangle is taken first when the cluster is empty, to keep spatial order
-                if (nt == 0) break;
+        cand.clear();
+
+        auto fresh_of = [&](uint32_t tt) {
+            const uint32_t* ix = indices + 3 * (size_t)tt;
+            uint32_t d = stamp[ix[0]] != c ? 1u : 0u;
+            if (ix[1] != ix[0] && stamp[ix[1]] != c) ++d;
+            if (ix[2] != ix[0] && ix[2] != ix[1] && stamp[ix[2]] != c) ++d;
+            return d;
+        };
+        float seed_c[3];
+        auto growth_of = [&](uint32_t tt) {
+            float g = 0.0f;
+            for (int a = 0; a < 3; ++a) {
+                float m = 0.0f;
+                for (int k = 0; k < 3; ++k) m += vertices[3 * (size_t)indices[3 * (size_t)tt + k] + a];
+                g = std::max(g, std::fabs(m * (1.0f / 3.0f) - seed_c[a]));
             }
-            if (best == 0xFFFFFFFFu || nv + best_new > kClusterVerts) break;
-            uint32_t t = (uint32_t)keyed[best];
-            taken[best] = 1;
+            return g;
+        };
+        auto add = [&](uint32_t tt) {
+            taken[tt] = 1;
             uint32_t li[3];
             for (int k = 0; k < 3; ++k) {
-                uint32_t vi = indices[3 * (size_t)t + k];
+                const uint32_t vi = indices[3 * (size_t)tt + k];
                 if (stamp[vi] != c) {
                     stamp[vi] = c;
                     local[vi] = (uint8_t)nv;
                     for (int a = 0; a < 3; ++a) {
-                        float f = vertices[3 * (size_t)vi + a];
+                        const float f = vertices[3 * (size_t)vi + a];
                         out.verts[vbase + 64 * a + nv] = f;
                         bl[a] = std::min(bl[a], f);
                         bh[a] = std::max(bh[a], f);
                     }
                     ++nv;
+                    for (uint32_t q = vstart[vi]; q < vstart[vi + 1]; ++q) {
+                        const uint32_t o = vtris[q];
+                        if (!taken[o] && listed[o] != c) {
+                            listed[o] = c;
+                            cand.push_back(o);
+                        }
+                    }
                 }
                 li[k] = local[vi];
             }
             out.tris[tbase + nt] = li[0] | (li[1] << 8) | (li[2] << 16);
-            out.tri_id[tbase + nt] = t;
+            out.tri_id[tbase + nt] = tt;
             ++nt;
+        };
+
+        for (int a = 0; a < 3; ++a) {
+            float m = 0.0f;
+            for (int k = 0; k < 3; ++k) m += vertices[3 * (size_t)indices[3 * (size_t)(uint32_t)keyed[head] + k] + a];
+            seed_c[a] = m * (1.0f / 3.0f);
+        }
+        add((uint32_t)keyed[head]);     // the seed keeps the clusters in spatial order
+        while (nt < kClusterTris) {
+            uint32_t best = 0xFFFFFFFFu, best_new = 4;
+            float best_grow = INFINITY;
+            size_t keep = 0;
+            for (size_t q = 0; q < cand.size(); ++q) {
+                const uint32_t tt = cand[q];
+                if (taken[tt]) continue;
+                cand[keep++] = tt;          // drop assigned triangles from the list as we go
+                const uint32_t fresh = fresh_of(tt);
+                if (fresh > best_new) continue;
+                const float grow = growth_of(tt);
+                if (fresh < best_new || grow < best_grow) {
+                    best_new = fresh;
+                    best_grow = grow;
+                    best = tt;
+                }
+            }
+            cand.resize(keep);
+            if (best == 0xFFFFFFFFu) {
+                // nothing connected is left: look at the next triangles of the spatial order
+                uint32_t seen = 0;
+                for (uint32_t p = head; p < T && seen < kWindow; ++p) {
+                    const uint32_t tt = (uint32_t)keyed[p];
+                    if (taken[tt]) continue;
+                    ++seen;
+                    const uint32_t fresh = fresh_of(tt);
+                    if (fresh < best_new) {
+                        best_new = fresh;
+                        best = tt;
+                        if (fresh == 0) break;
+                    }
+                }
+            }
+            if (best == 0xFFFFFFFFu || nv + best_new > kClusterVerts) break;
+            add(best);
         }
         for (uint32_t l = nv; l < kClusterVerts; ++l)
             for (int a = 0; a < 3; ++a) out.verts[vbase + 64 * a + l] = out.verts[vbase + 64 * a];
