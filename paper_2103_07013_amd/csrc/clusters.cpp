@@ -22,6 +22,54 @@ inline uint32_t spread10(uint32_t v) {  // 10 bits -> every third bit
 
 constexpr uint32_t kWindow = 192;  // look-ahead, in triangles
 
+// The renderer tests 64 consecutive clusters as one block.  Median splits along the longest axis of
+// the cluster centres, cut at multiples of 64, put clusters that are close in space into the same
+// block (much tighter block boxes than runs of a space-filling curve give).
+void split_blocks(std::vector<uint32_t>& order, size_t first, size_t last, const std::vector<float>& centre) {
+    const size_t n = last - first;
+    if (n <= 64) return;
+    float lo[3] = {INFINITY, INFINITY, INFINITY}, hi[3] = {-INFINITY, -INFINITY, -INFINITY};
+    for (size_t i = first; i < last; ++i)
+        for (int a = 0; a < 3; ++a) {
+            lo[a] = std::min(lo[a], centre[3 * (size_t)order[i] + a]);
+            hi[a] = std::max(hi[a], centre[3 * (size_t)order[i] + a]);
+        }
+    int axis = 0;
+    for (int a = 1; a < 3; ++a)
+        if (hi[a] - lo[a] > hi[axis] - lo[axis]) axis = a;
+    const size_t mid = first + ((n + 63) / 64 / 2) * 64;
+    std::nth_element(order.begin() + first, order.begin() + mid, order.begin() + last, [&](uint32_t x, uint32_t y) {
+        const float fx = centre[3 * (size_t)x + axis], fy = centre[3 * (size_t)y + axis];
+        return fx < fy || (fx == fy && x < y);
+    });
+    split_blocks(order, first, mid, centre);
+    split_blocks(order, mid, last, centre);
+}
+
+void order_for_blocks(ClusterSet& cs) {
+    if (cs.count <= 64) return;
+    std::vector<float> centre((size_t)cs.count * 3);
+    for (uint32_t c = 0; c < cs.count; ++c)
+        for (int a = 0; a < 3; ++a) centre[3 * (size_t)c + a] = 0.5f * (cs.bounds[6 * (size_t)c + a] + cs.bounds[6 * (size_t)c + 3 + a]);
+    std::vector<uint32_t> order(cs.count);
+    std::iota(order.begin(), order.end(), 0u);
+    split_blocks(order, 0, cs.count, centre);
+    ClusterSet out;
+    out.count = cs.count;
+    out.verts.resize(cs.verts.size());
+    out.tris.resize(cs.tris.size());
+    out.tri_id.resize(cs.tri_id.size());
+    out.bounds.resize(cs.bounds.size());
+    for (uint32_t c = 0; c < cs.count; ++c) {
+        const size_t s = order[c];
+        std::memcpy(&out.verts[(size_t)c * 192], &cs.verts[s * 192], 192 * sizeof(float));
+        std::memcpy(&out.tris[(size_t)c * 128], &cs.tris[s * 128], 128 * sizeof(uint32_t));
+        std::memcpy(&out.tri_id[(size_t)c * 128], &cs.tri_id[s * 128], 128 * sizeof(uint32_t));
+        std::memcpy(&out.bounds[(size_t)c * 6], &cs.bounds[s * 6], 6 * sizeof(float));
+    }
+    cs = std::move(out);
+}
+
 }  // namespace
 
 ClusterSet build_clusters(const float* vertices, uint32_t V, const uint32_t* indices, uint32_t T) {
@@ -52,11 +100,12 @@ ClusterSet build_clusters(const float* vertices, uint32_t V, const uint32_t* ind
 
     // ---- region growing
     // A cluster starts at the first unassigned triangle of the spatial order and grows by the
-    // triangle that costs least: fewest vertices not yet in the cluster first, then least growth of
-    // the cluster's bounding box (compact clusters have small screen footprints, which is what the
-    // renderer's culling tests look at).  Candidates are the unassigned triangles that touch a
-    // vertex of the cluster; where the mesh offers none (unconnected triangles) the next ones in
-    // spatial order stand in.
+    // triangle that costs least: fewest vertices not yet in the cluster first, then the one whose
+    // centroid is nearest the seed's in the maximum norm, which makes square axis-aligned patches
+    // (compact clusters have small boxes and small screen footprints, which is what the renderer's
+    // culling tests look at).  Candidates are the unassigned triangles that touch a vertex of the
+    // cluster; where the mesh offers none (unconnected triangles) the next ones in spatial order
+    // stand in.
     std::vector<uint32_t> vstart(V + 1, 0);
     for (size_t i = 0; i < (size_t)T * 3; ++i) ++vstart[indices[i] + 1];
     for (uint32_t v = 0; v < V; ++v) vstart[v + 1] += vstart[v];
@@ -183,6 +232,7 @@ ClusterSet build_clusters(const float* vertices, uint32_t V, const uint32_t* ind
         for (int a = 0; a < 3; ++a) out.bounds.push_back(bl[a]);
         for (int a = 0; a < 3; ++a) out.bounds.push_back(bh[a]);
     }
+    order_for_blocks(out);
     return out;
 }
 
