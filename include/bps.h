@@ -136,7 +136,11 @@ bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
  *   out_tri_id  DEVICE uint32 [B][H][W] or NULL; winning triangle id, 0xFFFFFFFF = none
  *   stream      hipStream_t (NULL = default stream)
  * Only enqueues work on `stream` and returns; host arrays are consumed before return, output
- * buffers must stay alive until the stream reaches the end of the request. */
+ * buffers must stay alive until the stream reaches the end of the request.
+ * Requests on one stream run in order.  Requests on different streams may overlap on the device
+ * (two requests in flight fill the compute units that the end of a launch leaves idle); the library
+ * itself orders those that use its internal buffers (RGB-D without out_tri_id, split frames,
+ * supersampling, diagnostics). */
 bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
                       float *out_depth, uint8_t *out_rgb, uint32_t *out_tri_id, void *stream);
 

@@ -104,6 +104,10 @@ struct bps_renderer {
     int plan_splits = 0;
     std::vector<bps::WorkItem> plan_items;
     uint64_t last_splits = 0, last_groups = 0;
+    // last request that used a buffer every request shares (ids, gvis, ss_*, d_stats): a later one on
+    // another stream waits for it
+    hipEvent_t shared_done = nullptr;
+    hipStream_t shared_stream = nullptr;
 };
 
 namespace {
@@ -133,13 +137,20 @@ void free_scene(HostScene& s) {
 }
 
 // Learn which requests have finished (never blocks) and recycle what they were holding.
+// Requests on different streams can finish out of order: everything up to the oldest request still
+// pending is complete (every request in flight holds a ring slot).
+void note_completions(bps_renderer* r) {
+    uint64_t all_done = r->seq;
+    for (const RingSlot& s : r->ring)
+        if (s.pending) all_done = std::min(all_done, s.seq - 1);
+    r->done_seq = std::max(r->done_seq, all_done);
+}
+
 void collect(bps_renderer* r) {
     for (RingSlot& s : r->ring)
-        if (s.pending && hipEventQuery(s.done) == hipSuccess) {
-            s.pending = false;
-            r->done_seq = std::max(r->done_seq, s.seq);
-        }
+        if (s.pending && hipEventQuery(s.done) == hipSuccess) s.pending = false;
     (void)hipGetLastError();
+    note_completions(r);
     for (size_t i = 0; i < r->retired.size();) {
         if (r->retired[i].last_use <= r->done_seq) {
             if (r->retired[i].arena.ptr) r->arena_pool.push_back(r->retired[i].arena);
@@ -714,7 +725,6 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     if (slot.pending) {
         BPS_HIP(r, hipEventSynchronize(slot.done));
         slot.pending = false;
-        r->done_seq = std::max(r->done_seq, slot.seq);
     }
     if (slot.capacity < need) {
         if (slot.host) (void)hipHostFree(slot.host);
@@ -753,6 +763,11 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         hipLaunchKernelGGL(bps::k_fill_keys, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, r->gvis, n);
         BPS_HIP(r, hipGetLastError());
     }
+
+    // Requests on one stream run in order.  A request on another stream may overlap the previous one
+    // unless both use one of the renderer's own buffers: then it waits for that one.
+    const bool uses_shared = (rgbd && out_tri_id == r->ids) || S > 1 || r->ss > 1 || r->want_stats;
+    if (uses_shared && r->shared_done && r->shared_stream != stream) BPS_HIP(r, hipStreamWaitEvent(stream, r->shared_done, 0));
 
     bps::FrameParams fp;
     fp.H = H;
@@ -820,6 +835,10 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     BPS_HIP(r, hipEventRecord(slot.done, stream));
     slot.pending = true;
     slot.seq = seq;
+    if (uses_shared) {
+        r->shared_done = slot.done;
+        r->shared_stream = stream;
+    }
     r->last_splits = (uint64_t)S;
     r->last_groups = (uint64_t)n_items;
     return BPS_OK;

@@ -181,3 +181,40 @@ def test_asynchronous_scene_rotation_while_rendering():
             assert np.array_equal(d[:8], refs[a]["depth"]) and np.array_equal(d[8:], refs[b]["depth"])
         assert all(bps.bps_scene_ready(r.handle, h) for h in live.values())
         assert bps.bps_query(r.handle, 0, 8) <= 4          # blocks were reused, not allocated per load
+
+
+@pytest.mark.parametrize("rgbd", [False, True])
+def test_requests_in_flight_on_two_streams(rgbd):
+    """Consecutive requests on two alternating streams may overlap on the device.  Every frame must
+    still match the oracle, also where requests share the renderer's own buffers (RGB-D) and where a
+    scene is retired while requests on both streams still read it."""
+    import torch
+    import oracle
+    import paper_2103_07013_amd as bps
+    scenes = [synth.make_multiroom_scene(40_000, seed=1300 + k) for k in range(3)]
+    cams = [synth.make_cameras(sc, 24, seed=5 + k)[0] for k, sc in enumerate(scenes)]
+    refs = [oracle.render_scene(sc.vertices, sc.indices, cams[k], 64, 64, colors=sc.colors if rgbd else None)
+            for k, sc in enumerate(scenes)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    mode = bps.MODE_RGBD if rgbd else bps.MODE_DEPTH
+    with bps.Renderer(max_batch=24, mode=mode) as r:
+        handles = [r.load_scene(sc.vertices, sc.indices, sc.colors if rgbd else None) for sc in scenes[:2]]
+        live = [0, 1]
+        outs = []
+        for step in range(10):
+            k = live[step % 2]
+            n = 24 - (step % 3) * 5                       # batch sizes 24, 19, 14
+            depth = torch.empty((n, 64, 64), dtype=torch.float32, device="cuda")
+            rgb = torch.empty((n, 64, 64, 3), dtype=torch.uint8, device="cuda") if rgbd else None
+            ids = np.full(n, handles[live.index(k)], np.int32)
+            bps.bps_render(r.handle, ids, cams[k][:n], depth, out_rgb=rgb, stream=streams[step % 2])
+            outs.append((k, n, depth, rgb))
+            if step == 5:                                 # scene 0 leaves while both streams are busy
+                r.unload_scene(handles[0])
+                handles[0] = r.load_scene(scenes[2].vertices, scenes[2].indices, scenes[2].colors if rgbd else None)
+                live[0] = 2
+        torch.cuda.synchronize()
+        for step, (k, n, depth, rgb) in enumerate(outs):
+            assert np.array_equal(depth.cpu().numpy(), refs[k]["depth"][:n]), f"request {step}"
+            if rgbd:
+                assert np.array_equal(rgb.cpu().numpy(), refs[k]["rgb"][:n]), f"request {step}"
