@@ -62,6 +62,7 @@ struct RingSlot {
     hipEvent_t done = nullptr;
     bool pending = false;
     uint64_t seq = 0;
+    uint64_t items_version = 0;      // plan whose work items the device buffer holds (0 = none)
 };
 
 }  // namespace
@@ -102,6 +103,7 @@ struct bps_renderer {
     // cached plan: valid while the scene ids and split count repeat
     std::vector<bps_scene> plan_ids;
     int plan_splits = 0;
+    uint64_t plan_version = 0;        // counts the plans made; ring slots remember which one they hold
     std::vector<bps::WorkItem> plan_items;
     uint64_t last_splits = 0, last_groups = 0;
     // last request that used a buffer every request shares (ids, gvis, ss_*, d_stats): a later one on
@@ -704,6 +706,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         }
         r->plan_ids.assign(scene_ids, scene_ids + B);
         r->plan_splits = S;
+        ++r->plan_version;
     }
     const size_t n_items = r->plan_items.size();
 
@@ -735,19 +738,31 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         BPS_HIP(r, hipHostMalloc((void**)&slot.host, cap, hipHostMallocDefault));
         BPS_HIP(r, hipMalloc((void**)&slot.dev, cap));
         slot.capacity = cap;
+        slot.items_version = 0;
     }
-    std::memcpy(slot.host, r->plan_items.data(), items_bytes);
-    if (rgbd) std::memcpy(slot.host + items_bytes, scene_ids, ids_bytes);
-    size_t copy_bytes = items_bytes + ids_bytes;
+    unsigned char* const payload = slot.dev;
+    // The work items only change with the scene ids: each slot keeps the copy it has until then, so
+    // a depth request whose matrices are on the device stages nothing at all.
+    size_t copy_from = items_bytes, copy_to = items_bytes;
+    if (slot.items_version != r->plan_version) {
+        std::memcpy(slot.host, r->plan_items.data(), items_bytes);
+        copy_from = 0;
+    }
+    if (rgbd) {
+        std::memcpy(slot.host + items_bytes, scene_ids, ids_bytes);
+        copy_to = items_bytes + ids_bytes;
+    }
     if (!vp_on_device) {
-        std::memcpy(slot.host + copy_bytes, view_proj, vp_bytes);
-        copy_bytes += vp_bytes;
+        std::memcpy(slot.host + items_bytes + ids_bytes, view_proj, vp_bytes);
+        copy_to = items_bytes + ids_bytes + vp_bytes;
     }
-    BPS_HIP(r, hipMemcpyAsync(slot.dev, slot.host, copy_bytes, hipMemcpyHostToDevice, stream));
-    const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(slot.dev);
-    const uint32_t* d_env_scene = reinterpret_cast<const uint32_t*>(slot.dev + items_bytes);
-    const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(slot.dev + items_bytes + ids_bytes);
-    uint32_t* d_cost = reinterpret_cast<uint32_t*>(slot.dev + items_bytes + ids_bytes + vp_bytes);
+    if (copy_to > copy_from)
+        BPS_HIP(r, hipMemcpyAsync(payload + copy_from, slot.host + copy_from, copy_to - copy_from, hipMemcpyHostToDevice, stream));
+    slot.items_version = r->plan_version;
+    const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(payload);
+    const uint32_t* d_env_scene = reinterpret_cast<const uint32_t*>(payload + items_bytes);
+    const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(payload + items_bytes + ids_bytes);
+    uint32_t* d_cost = reinterpret_cast<uint32_t*>(payload + items_bytes + ids_bytes + vp_bytes);
     uint32_t* d_dispatch = planned ? d_cost + n_items : nullptr;
 
     // ---- RGB-D: the colour pass needs the winning triangle ids even when the caller does not
