@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4      # wave64 vector instructions per second: 256 CUs x 4 SIMDs, 4 cycles each
 
 
 def full_stream_bytes(w):
@@ -281,9 +282,17 @@ def main():
         if nbytes is None:
             return None
         achieved = nbytes / (ms * 1e-3) / 1e9
-        return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(traffic_key), "kernel": "k_raster",
-                "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes, "accounting": note}
+        out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+               "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(traffic_key), "kernel": "k_raster",
+               "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes, "accounting": note}
+        valu = measured_traffic(traffic_key + "_valu_insts")
+        if valu:
+            # what the counters say binds the kernel: vector-ALU issue (1024 SIMDs, 4 cycles per wave64 instruction)
+            peak = VALU_ISSUE_PEAK
+            out["valu_issue"] = {"insts_per_launch": valu, "achieved_Ginst_s": valu / (ms * 1e-3) / 1e9,
+                                 "peak_Ginst_s": peak / 1e9, "frac": valu / (ms * 1e-3) / peak,
+                                 "note": "SQ_INSTS_VALU from the rocprofv3 run under profiles/ over this run's kernel time"}
+        return out
 
     def copy_ceiling_gbs():
         """Read + write rate of a plain 1 GiB device-to-device copy: what a pure streaming kernel gets."""
