@@ -21,6 +21,10 @@ inline uint32_t spread10(uint32_t v) {  // 10 bits -> every third bit
 }
 
 constexpr uint32_t kWindow = 192;  // look-ahead, in triangles
+// Candidate triangles kept per growing cluster.  Ordinary meshes stay far below it; the bound keeps
+// the work per cluster fixed on meshes with vertices of enormous valence (triangles left out are
+// simply picked up by a later cluster).
+constexpr size_t kMaxCandidates = 512;
 
 // The renderer tests 64 consecutive clusters as one block.  Median splits along the longest axis of
 // the cluster centres, cut at multiples of 64, put clusters that are close in space into the same
@@ -115,6 +119,7 @@ ClusterSet build_clusters(const float* vertices, uint32_t V, const uint32_t* ind
         for (uint32_t tt = 0; tt < T; ++tt)
             for (int k = 0; k < 3; ++k) vtris[fill[indices[3 * (size_t)tt + k]]++] = tt;
     }
+    std::vector<uint32_t> vfirst(vstart.begin(), vstart.end() - 1);   // first entry of a vertex's list that may be free
     std::vector<uint32_t> stamp(V, 0xFFFFFFFFu);     // cluster that last used the vertex
     std::vector<uint8_t> local(V, 0);
     std::vector<uint8_t> taken(T, 0);                // by triangle
@@ -169,7 +174,10 @@ ClusterSet build_clusters(const float* vertices, uint32_t V, const uint32_t* ind
                         bh[a] = std::max(bh[a], f);
                     }
                     ++nv;
-                    for (uint32_t q = vstart[vi]; q < vstart[vi + 1]; ++q) {
+                    // triangles once taken stay taken: skip the taken head of the vertex's list for good
+                    uint32_t& from = vfirst[vi];
+                    while (from < vstart[vi + 1] && taken[vtris[from]]) ++from;
+                    for (uint32_t q = from; q < vstart[vi + 1] && cand.size() < kMaxCandidates; ++q) {
                         const uint32_t o = vtris[q];
                         if (!taken[o] && listed[o] != c) {
                             listed[o] = c;
