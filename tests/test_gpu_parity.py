@@ -312,3 +312,33 @@ def test_random_soup_rgbd_and_texture_through_the_clipper():
     assert np.array_equal(gi[:10], ref_c["tri_id"]) and np.array_equal(gi[10:], ref_t["tri_id"])
     assert np.array_equal(g[:10], ref_c["rgb"])
     assert np.array_equal(g[10:], ref_t["rgb"])
+
+
+@pytest.mark.parametrize("seed,H,W", [(31, 64, 64), (32, 128, 128), (33, 48, 104)])
+def test_connected_scene_under_arbitrary_cameras(seed, H, W):
+    """A connected mesh (clusters grown over shared vertices, occlusion between rooms) seen by cameras
+    anywhere in it, also inside objects and walls, with pitch, roll, narrow to very wide fields of view
+    and near planes that cut the geometry; culling on and off must both equal the oracle."""
+    import oracle
+    import paper_2103_07013_amd as bps
+    rng = np.random.default_rng(seed)
+    scene = synth.make_multiroom_scene(40_000, seed=1400 + seed)
+    lo, hi = scene.vertices.min(0), scene.vertices.max(0)
+    Ms = []
+    for k in range(16):
+        pos = rng.uniform(lo, hi)
+        yaw, pitch, roll = rng.uniform(0, 2 * np.pi), rng.uniform(-1.4, 1.4), rng.uniform(-np.pi, np.pi)
+        hfov = float(rng.choice([20.0, 60.0, 90.0, 150.0, 175.0]))
+        near = float(rng.choice([0.01, 0.5, 3.0]))
+        P = synth.perspective(hfov, W / H, near, near + float(rng.choice([4.0, 20.0, 100.0])))
+        V = synth.look_yaw(pos, yaw, pitch)
+        c, s = np.cos(roll), np.sin(roll)
+        R = np.eye(4)
+        R[0, 0], R[0, 1], R[1, 0], R[1, 1] = c, -s, s, c
+        Ms.append((P @ R @ V).astype(np.float32))
+    Ms = np.stack(Ms)
+    ref = oracle.render_scene(scene.vertices, scene.indices, Ms, H, W)
+    for flags in (0, bps.FLAG_NO_OCCLUSION_CULL, bps.FLAG_NO_CLUSTER_CULL):
+        gd, gi, _ = _render_gpu([scene], [0] * 16, Ms, H, W, flags=flags)
+        _compare(gd, gi, ref, f"seed {seed} {H}x{W} flags={flags}")
+    assert (ref["tri_id"] != NOHIT).mean() > 0.3
