@@ -638,10 +638,18 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             for (uint32_t i = tid; i < n_list; i += NT)
                 slot_in_bin[i] = (uint16_t)atomicAdd(&hist[depth_bin(list[i])], 1u);
             __syncthreads();
-            if (tid < kDepthBins) {
-                uint32_t before = 0;
-                for (int b = 0; b < tid; ++b) before += hist[b];
-                hist[kDepthBins + tid] = before;
+            if (wave == 0) {   // exclusive prefix sums of the bins: two bins per lane, shuffle scan of the pair sums
+                static_assert(kDepthBins == 128, "one wavefront scans two bins per lane");
+                const uint32_t h0 = hist[2 * lane], h1 = hist[2 * lane + 1];
+                uint32_t incl = h0 + h1;
+#pragma unroll
+                for (int step = 1; step < 64; step <<= 1) {
+                    const uint32_t up = (uint32_t)__shfl_up((int)incl, step, 64);
+                    if (lane >= step) incl += up;
+                }
+                const uint32_t before = incl - (h0 + h1);
+                hist[kDepthBins + 2 * lane] = before;
+                hist[kDepthBins + 2 * lane + 1] = before + h0;
             }
             __syncthreads();
             for (uint32_t i = tid; i < n_list; i += NT)
