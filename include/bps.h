@@ -165,8 +165,8 @@ bps_status bps_kernel_ms_each(bps_renderer *r, float *out, uint32_t capacity, ui
  *   [6] small triangles queued for per-lane rasterisation   [7] large triangles rasterised by a wavefront
  *   [8] clusters rejected against the coarse depth tiles before being queued
  *   [9..15] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
- *           in the bounds testing, barrier, depth sort, (unused), cluster processing, barrier
- *           and flush phases.
+ *           in the bounds testing, barrier, depth sort, prologue (set-up and block ordering),
+ *           cluster processing, barrier and final flush phases.
  *   with enable = 1 instead: [11] environment index, [12] run times of all the group's wavefronts
  *           summed, [13] start and [14] end of the group on the device-wide 100 MHz clock (low 32
  *           bits), [15] hardware id of the compute unit that ran it (die in the top byte).

@@ -325,16 +325,29 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     }
     int cnt = have ? 3 : 0;
     int cur = 0;
-    const int order[6] = {4, 5, 0, 1, 2, 3};
-    for (int oi = 0; oi < 6; ++oi) {
-        int k = order[oi];
-        if (!((oc_or >> k) & 1u) || cnt < 3) continue;
+    // Planes are taken in the rule's order near, far, left, right, top, bottom, but every lane only
+    // visits the planes its own triangle crosses: in pass j each lane clips against the j-th of
+    // them, so a wavefront of triangles that each cross one (different) plane needs one pass, not six.
+    // The plane is applied as c.x x + c.y y + c.z z + c.w w with coefficients 0 and +-1, which rounds
+    // exactly like the written-out w + x, w - x, ..., z, w - z (products with 0 and +-1 and sums
+    // with 0 are exact).
+    uint32_t todo = ((oc_or >> 4) & 3u) | ((oc_or & 15u) << 2);      // bit p: p-th plane of the order
+    if (cnt < 3) todo = 0u;
+    while (ballot64(todo != 0u) != 0ull) {
+        const bool active = todo != 0u;
+        const int p = active ? __builtin_ctz(todo) : 0;
+        todo &= todo - 1u;
+        const int k = p < 2 ? p + 4 : p - 2;                         // plane number: 4 5 0 1 2 3
+        const float cx = k == 0 ? 1.0f : k == 1 ? -1.0f : 0.0f, cy = k == 2 ? 1.0f : k == 3 ? -1.0f : 0.0f;
+        const float cz = k == 4 ? 1.0f : k == 5 ? -1.0f : 0.0f, cw = k == 4 ? 0.0f : 1.0f;
+        auto dist = [&](const Clip4& q) { return fmaf(cx, q.x, fmaf(cy, q.y, fmaf(cz, q.z, cw * q.w))); };
+        if (!active) continue;
         int m = 0;
         Clip4 prev = px[cur][cnt - 1];
-        float dprev = plane_dist(prev, k);
+        float dprev = dist(prev);
         for (int i = 0; i < cnt; ++i) {
             Clip4 v = px[cur][i];
-            float dv = plane_dist(v, k);
+            float dv = dist(v);
             bool cin = dv >= 0.0f, pin = dprev >= 0.0f;
             if (cin != pin && m < kMaxPoly) {
                 // always from the inside vertex a to the outside vertex b
@@ -354,6 +367,7 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
         }
         cnt = m;
         cur ^= 1;
+        if (cnt < 3) todo = 0u;
     }
     if (cnt < 3) cnt = 0;
     // project every polygon vertex; one failure drops the triangle
@@ -540,7 +554,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     //            list until enough are queued or the list could overflow
     //   phase B  wavefronts pop clusters from the list one at a time; a cluster whose footprint
     //            pixels all hold nearer depths by then is skipped (one lane per footprint pixel)
-    TICK(0);
+    TICK(4);
     // the first round is kept short: what it draws (the nearest blocks) lets later rounds reject
     // hidden clusters before they are queued
     uint32_t round_target = occlusion ? min((uint32_t)fp.round_target, (uint32_t)fp.first_round) : (uint32_t)fp.round_target;
@@ -803,6 +817,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         wave_lds_sync();
         drain_small(L, small_count, lane, vis, win, g_ctri_id);
     }
+    TICK(7);
     // diagnostics: per-wave tallies go through LDS (the survivor list is free by now) and leave as
     // one record of 16 words per work-group, without atomics
     if (stats && lane == 0) {
