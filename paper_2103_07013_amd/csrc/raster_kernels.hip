@@ -640,7 +640,10 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         __syncthreads();
         TICK(2);
         const uint32_t n_list = *list_count;
-        if (n_list == 0 && *next_block >= nb_visit) break;
+        // every block has been handed out: this is the last round (the same for all wavefronts:
+        // next_block only moves during phase A)
+        const bool last_round = *next_block >= nb_visit;
+        if (n_list == 0 && last_round) break;
         st_boxed += wave == 0 ? n_list : 0u;
 
         // Order the round's survivors near to far (counting sort on a logarithmic depth key, eight
@@ -790,9 +793,13 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             }
         }
         TICK(5);
+        // After the last round a wavefront goes straight on to flush its queues, without waiting for
+        // the others: the flush (one pass of the clipper, mostly waiting for memory) then overlaps the
+        // clusters the slower wavefronts are still drawing.
+        if (last_round) break;
         __syncthreads();
         if (tid == 0) { *list_count = 0u; *pop_count = 0u; *reserved = 0u; }
-        if (occlusion && *next_block < nb_visit) {
+        if (occlusion) {   // (more blocks are waiting, or the loop would have ended above)
             // Hi-Z: largest stored depth word per 8x8-pixel tile of the window (empty pixels read as
             // 0xFFFFFFFF); one wavefront per tile, butterfly maximum
             const int hty = (win.h + 7) >> 3;
@@ -818,6 +825,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         drain_small(L, small_count, lane, vis, win, g_ctri_id);
     }
     TICK(7);
+    if (stats) __syncthreads();   // the record below reuses the survivor list: every wavefront must be done with it
     // diagnostics: per-wave tallies go through LDS (the survivor list is free by now) and leave as
     // one record of 16 words per work-group, without atomics
     if (stats && lane == 0) {
