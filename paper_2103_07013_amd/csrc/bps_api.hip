@@ -721,7 +721,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     // costliest-first dispatch pays off once the launch no longer fits on the device in one go
     const bool planned = fp_cull_enabled(r) && n_items > (size_t)2 * r->num_cu && n_items <= bps::kMaxPlannedItems &&
                          !(r->cfg.flags & BPS_FLAG_NO_DISPATCH_ORDER);
-    const size_t plan_bytes = planned ? 2 * n_items * sizeof(uint32_t) : 0;
+    const size_t plan_bytes = planned ? n_items * (sizeof(bps::WorkItem) + 2 * sizeof(uint32_t)) + 16 : 0;
     const size_t need = items_bytes + ids_bytes + vp_bytes + plan_bytes;
     RingSlot& slot = r->ring[r->ring_next];
     r->ring_next = (r->ring_next + 1) % kRing;
@@ -762,8 +762,11 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(payload);
     const uint32_t* d_env_scene = reinterpret_cast<const uint32_t*>(payload + items_bytes);
     const float* d_vp = vp_on_device ? view_proj : reinterpret_cast<const float*>(payload + items_bytes + ids_bytes);
-    uint32_t* d_cost = reinterpret_cast<uint32_t*>(payload + items_bytes + ids_bytes + vp_bytes);
-    uint32_t* d_dispatch = planned ? d_cost + n_items : nullptr;
+    // planning area: the items in launch order (16-byte aligned), then cost and order words
+    const size_t plan_at = (items_bytes + ids_bytes + vp_bytes + 15) & ~(size_t)15;
+    bps::WorkItem* d_ordered = reinterpret_cast<bps::WorkItem*>(payload + plan_at);
+    uint32_t* d_cost = reinterpret_cast<uint32_t*>(d_ordered + n_items);
+    uint32_t* d_dispatch = d_cost + n_items;
 
     // ---- RGB-D: the colour pass needs the winning triangle ids even when the caller does not
     if (rgbd && !out_tri_id) {
@@ -826,11 +829,11 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         r->ev_used += 2;
     }
     if (planned) {
-        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch);
+        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
         BPS_HIP(r, hipGetLastError());
     }
-    bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, d_items, d_vp, fp, r->gvis, out_depth,
-                       out_tri_id, d_stats, d_dispatch);
+    bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, planned ? d_ordered : d_items, d_vp, fp,
+                       r->gvis, out_depth, out_tri_id, d_stats);
     BPS_HIP(r, hipGetLastError());
     if (S > 1) {
         size_t n = (size_t)B * HW;

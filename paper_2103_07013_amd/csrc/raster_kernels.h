@@ -86,7 +86,7 @@ template <int NT, bool DIAG, int CULL, bool WHOLE64>
 __global__ void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                          const float* __restrict__ view_proj, FrameParams fp, unsigned long long* __restrict__ gvis,
                          float* __restrict__ out_depth, uint32_t* __restrict__ out_id,
-                         unsigned long long* __restrict__ stats, const uint32_t* __restrict__ dispatch);
+                         unsigned long long* __restrict__ stats);
 
 __global__ void k_resolve(unsigned long long* __restrict__ gvis, size_t n, float background,
                           float* __restrict__ out_depth, uint32_t* __restrict__ out_id);
@@ -96,12 +96,12 @@ __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n);
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
-                   uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch);
-// Fills dispatch[n_items] with the item indices in launch order, costliest first; cost is scratch,
-// one word per item.
+                   uint32_t* out_id, unsigned long long* stats);
+// Fills ordered[n_items] with the items in launch order, costliest first; cost and dispatch are
+// scratch, one word per item each.
 constexpr uint32_t kMaxPlannedItems = 16384;
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
-                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch);
+                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch, WorkItem* ordered);
 hipError_t prepare_raster(int threads, size_t lds);
 void launch_downsample(hipStream_t stream, const float* depth, const uint8_t* rgb, uint32_t B, int H, int W,
                        float* out_depth, uint8_t* out_rgb);

@@ -408,8 +408,7 @@ template <int NT, bool DIAG, int CULL, bool WHOLE64>
 __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
-                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats_block,
-                                               const uint32_t* __restrict__ dispatch) {
+                                               uint32_t* __restrict__ out_id, unsigned long long* __restrict__ stats_block) {
     extern __shared__ __align__(16) unsigned char smem[];
     // The DIAG = false instance carries no counters or timers at all: everything below that feeds
     // only the diagnostics record is dead code there and costs neither registers nor instructions.
@@ -453,7 +452,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     uint32_t* reserved = counters + 3;     // upper bound on list_count once every tester has appended
     uint32_t* blocks_in_view = counters + 4;   // blocks of the item that are not wholly outside the frustum
 
-    const WorkItem item = items[dispatch ? dispatch[blockIdx.x] : blockIdx.x];
+    const WorkItem item = items[blockIdx.x];     // the host or the planner has put the items in launch order
     const SceneDev sc = scenes[item.scene];
     float M[16];
 #pragma unroll
@@ -928,7 +927,8 @@ __global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ s
 // buckets): consecutive work-group indices go to consecutive dies, so every die receives an even
 // sample of the cost distribution, costliest first.
 __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restrict__ cost, uint32_t n_items,
-                                                         uint32_t* __restrict__ dispatch) {
+                                                         uint32_t* __restrict__ dispatch, const WorkItem* __restrict__ items,
+                                                         WorkItem* __restrict__ ordered) {
     constexpr uint32_t kBuckets = 2048;
     __shared__ uint32_t bucket[kBuckets];
     __shared__ uint32_t scan[1024];
@@ -1008,14 +1008,17 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        dispatch[base + lane] = mine[lane];
+        // the raster kernel reads its item at its own work-group index: one dependent load fewer
+        // than going through the order
+        ordered[base + lane] = items[mine[lane]];
     }
+    for (uint32_t i = (n_items & ~63u) + tid; i < n_items; i += 1024u) ordered[i] = items[dispatch[i]];
 }
 
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
-                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch) {
+                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch, WorkItem* ordered) {
     hipLaunchKernelGGL(k_item_cost, dim3(n_items), dim3(64), 0, stream, scenes, items, view_proj, fp, n_items, cost);
-    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), 0, stream, cost, n_items, dispatch);
+    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), 0, stream, cost, n_items, dispatch, items, ordered);
 }
 
 __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n) {
@@ -1051,17 +1054,17 @@ hipError_t prepare_raster(int threads, size_t lds) {
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
-                   uint32_t* out_id, unsigned long long* stats, const uint32_t* dispatch) {
+                   uint32_t* out_id, unsigned long long* stats) {
     // 64x64 frames in the default configuration have an instance of their own
     if (threads == 512 && !stats && fp.cull == 2 && fp.W == 64 && fp.H == 64 && fp.tile_w == 64 && fp.tile_h == 64 &&
         fp.list_cap == (int)kListCap64) {
         hipLaunchKernelGGL((k_raster<512, false, 2, true>), grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis,
-                           out_depth, out_id, stats, dispatch);
+                           out_depth, out_id, stats);
         return;
     }
 #define BPS_LAUNCH3(NT, DIAG, CULL)                                                                                    \
     hipLaunchKernelGGL((k_raster<NT, DIAG, CULL, false>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,      \
-                       out_depth, out_id, stats, dispatch)
+                       out_depth, out_id, stats)
 #define BPS_LAUNCH2(NT, DIAG)                                                                                          \
     do {                                                                                                               \
         if (fp.cull == 0) BPS_LAUNCH3(NT, DIAG, 0);                                                                    \
