@@ -576,6 +576,10 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 break;
             }
             const uint32_t jb = sorted ? (uint32_t)order[blk] : blk;
+            if (occlusion && jb == 0xFFFFu) {      // struck out: the whole block is hidden
+                if (lane == 0) atomicSub(reserved, 64u);
+                continue;
+            }
             const uint32_t cl = (jb * S + item_split) * 64u + (uint32_t)lane;
             bool visible = cl < sc.n_clusters;
             uint32_t foot = 0u, wb18 = 0u;
@@ -799,6 +803,20 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         __syncthreads();
         if (tid == 0) { *list_count = 0u; *pop_count = 0u; *reserved = 0u; }
         if (occlusion) {   // (more blocks are waiting, or the loop would have ended above)
+            // Whole blocks are tested against the new depth tiles as well: thread k takes the k-th block
+            // still waiting.  Its bounds are fetched now and arrive while the tiles are being built.
+            const uint32_t waiting_from = *next_block;      // stable: it only moves during phase A
+            float blo[3] = {0.0f, 0.0f, 0.0f}, bhi[3] = {0.0f, 0.0f, 0.0f};
+            uint32_t my_rank = waiting_from + (uint32_t)tid;
+            bool my_block = sorted && my_rank < nb_visit && order[my_rank] != 0xFFFFu;
+            if (my_block) {
+                const uint32_t gb = (uint32_t)order[my_rank] * S + item_split;
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    blo[a] = g_bbounds[(size_t)a * sc.b_stride + gb];
+                    bhi[a] = g_bbounds[(size_t)(a + 3) * sc.b_stride + gb];
+                }
+            }
             // Hi-Z: largest stored depth word per 8x8-pixel tile of the window (empty pixels read as
             // 0xFFFFFFFF); one wavefront per tile, butterfly maximum
             const int hty = (win.h + 7) >> 3;
@@ -808,6 +826,24 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 #pragma unroll
                 for (int sh = 32; sh >= 1; sh >>= 1) dbits = max(dbits, (uint32_t)__shfl_xor((int)dbits, sh, 64));
                 if (lane == 0) hiz[t] = dbits;
+            }
+            __syncthreads();
+            // A block whose box lies behind the largest depth of every tile its footprint touches hides
+            // all of its clusters (their boxes are inside it; depths only ever decrease): its entry in
+            // the visiting order is struck out and phase A passes over it.
+            if (my_block) {
+                uint32_t wb18 = 0u;
+                const uint32_t foot = box_footprint(M, fq, win, blo[0], blo[1], blo[2], bhi[0], bhi[1], bhi[2], wb18);
+                bool dead = foot == kNoPixel;
+                if (!dead && (foot & 1u)) {
+                    const int fx = (int)((foot >> 1) & 63u), fy = (int)((foot >> 7) & 63u);
+                    const int bw = (int)((foot >> 13) & 31u), bh = (int)((foot >> 18) & 31u);
+                    uint32_t zmax = 0u;
+                    for (int ty = fy >> 3; ty <= (fy + bh) >> 3; ++ty)
+                        for (int tx = fx >> 3; tx <= (fx + bw) >> 3; ++tx) zmax = max(zmax, hiz[ty * htx + tx]);
+                    dead = (wb18 << 13) > zmax;
+                }
+                if (dead) order[my_rank] = 0xFFFFu;
             }
         }
         round_target = (uint32_t)fp.round_target;
