@@ -345,8 +345,10 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
         int m = 0;
         Clip4 prev = px[cur][cnt - 1];
         float dprev = dist(prev);
+        Clip4 ahead = px[cur][0];            // the polygon lives in private memory: fetch one vertex ahead
         for (int i = 0; i < cnt; ++i) {
-            Clip4 v = px[cur][i];
+            Clip4 v = ahead;
+            ahead = px[cur][min(i + 1, kMaxPoly - 1)];
             float dv = dist(v);
             bool cin = dv >= 0.0f, pin = dprev >= 0.0f;
             if (cin != pin && m < kMaxPoly) {
@@ -374,22 +376,39 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     uint32_t pxy[kMaxPoly];
     float piw[kMaxPoly];
     bool ok = true;
-    for (int i = 0; i < cnt; ++i) {
+    for (int i = 0; i < cnt; i += 2) {      // two vertices per step: both fetches are in flight together
+        const Clip4 q0 = px[cur][i], q1 = px[cur][min(i + 1, kMaxPoly - 1)];
         bool unused;
-        ok = project(px[cur][i], fp, pxy[i], piw[i], unused) && ok;
+        uint32_t xy0, xy1;
+        float iw0, iw1;
+        ok = project(q0, fp, xy0, iw0, unused) && ok;
+        pxy[i] = xy0; piw[i] = iw0;
+        if (i + 1 < cnt) {
+            ok = project(q1, fp, xy1, iw1, unused) && ok;
+            pxy[i + 1] = xy1; piw[i + 1] = iw1;
+        }
     }
     if (!ok) cnt = 0;
     const BPS_GLOBAL uint32_t* ctri_id = gptr(sc.ctri_id);
     const uint32_t tri_ref = c * 128u + slot;
+    // fan (0, i, i + 1): vertex i is the previous piece's last one, and the next one is fetched ahead
+    const uint32_t a = pxy[0];
+    const float wa = piw[0];
+    uint32_t b = pxy[1], d_ahead = pxy[2];
+    float wb = piw[1], wd_ahead = piw[2];
     for (int i = 1; ; ++i) {
         bool v = i + 1 < cnt;
         const u64 vm = ballot64(v);
         if (vm == 0) break;
-        uint32_t a = v ? pxy[0] : 0u, b = v ? pxy[i] : 0u, d = v ? pxy[i + 1] : 0u;
-        float wa = v ? piw[0] : 0.0f, wb = v ? piw[i] : 0.0f, wd = v ? piw[i + 1] : 0.0f;
+        const uint32_t d = d_ahead;
+        const float wd = wd_ahead;
+        d_ahead = pxy[min(i + 2, kMaxPoly - 1)];
+        wd_ahead = piw[min(i + 2, kMaxPoly - 1)];
         short2v lo, ext;
-        const bool has = centre_box(a, b, d, win, lo, ext);
-        emit(L, small_count, v && has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, win, vm & ballot64(has));
+        const bool has = v && centre_box(a, b, d, win, lo, ext);
+        emit(L, small_count, has, lo, ext, a, b, d, wa, wb, wd, tri_ref, ctri_id, lane, vis, win, ballot64(has));
+        b = d;
+        wb = wd;
     }
 }
 
