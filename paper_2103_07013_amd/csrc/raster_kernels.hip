@@ -316,13 +316,22 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     uint32_t c = ref >> 7, slot = ref & 127u;
     uint32_t t = gptr(sc.ctris)[(size_t)c * 128 + slot] & 0x00FFFFFFu;
     const BPS_GLOBAL float* cv = gptr(sc.cverts) + (size_t)c * 192;
-    Clip4 px[2][kMaxPoly];
+    Clip4 tri[3];
     uint32_t oc_or = 0;
+#pragma unroll
     for (int k = 0; k < 3; ++k) {
         uint32_t vi = (t >> (8 * k)) & 0xFFu;
-        px[0][k] = to_clip(M, cv[vi], cv[64 + vi], cv[128 + vi]);
-        oc_or |= outcode(px[0][k]);
+        tri[k] = to_clip(M, cv[vi], cv[64 + vi], cv[128 + vi]);
+        oc_or |= outcode(tri[k]);
     }
+    // Polygons between passes live in private memory, and a value stored there comes back only after
+    // a trip to L2.  So the first pass takes the triangle from registers, and a lane's last pass
+    // projects the vertices it puts out at once (one failure drops the triangle) instead of storing
+    // them for a separate projection loop: a triangle that crosses one plane never reads a polygon back.
+    Clip4 px[2][kMaxPoly];
+    uint32_t pxy[kMaxPoly];
+    float piw[kMaxPoly];
+    bool ok = true;
     int cnt = have ? 3 : 0;
     int cur = 0;
     // Planes are taken in the rule's order near, far, left, right, top, bottom, but every lane only
@@ -333,62 +342,84 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     // with 0 are exact).
     uint32_t todo = ((oc_or >> 4) & 3u) | ((oc_or & 15u) << 2);      // bit p: p-th plane of the order
     if (cnt < 3) todo = 0u;
+    if (ballot64(have && todo == 0u) != 0ull) {      // crosses no plane after all: the triangle as it is
+        if (have && todo == 0u) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                bool unused;
+                ok = project(tri[k], fp, pxy[k], piw[k], unused) && ok;
+            }
+        }
+    }
+    bool first_pass = true;
     while (ballot64(todo != 0u) != 0ull) {
         const bool active = todo != 0u;
         const int p = active ? __builtin_ctz(todo) : 0;
         todo &= todo - 1u;
+        const bool last = todo == 0u;                                // this lane's final plane
         const int k = p < 2 ? p + 4 : p - 2;                         // plane number: 4 5 0 1 2 3
         const float cx = k == 0 ? 1.0f : k == 1 ? -1.0f : 0.0f, cy = k == 2 ? 1.0f : k == 3 ? -1.0f : 0.0f;
         const float cz = k == 4 ? 1.0f : k == 5 ? -1.0f : 0.0f, cw = k == 4 ? 0.0f : 1.0f;
         auto dist = [&](const Clip4& q) { return fmaf(cx, q.x, fmaf(cy, q.y, fmaf(cz, q.z, cw * q.w))); };
-        if (!active) continue;
-        int m = 0;
-        Clip4 prev = px[cur][cnt - 1];
-        float dprev = dist(prev);
-        Clip4 ahead = px[cur][0];            // the polygon lives in private memory: fetch one vertex ahead
-        for (int i = 0; i < cnt; ++i) {
-            Clip4 v = ahead;
-            ahead = px[cur][min(i + 1, kMaxPoly - 1)];
-            float dv = dist(v);
-            bool cin = dv >= 0.0f, pin = dprev >= 0.0f;
-            if (cin != pin && m < kMaxPoly) {
-                // always from the inside vertex a to the outside vertex b
-                Clip4 a = cin ? v : prev, b = cin ? prev : v;
-                float da = cin ? dv : dprev, db = cin ? dprev : dv;
-                float tt = da / (da - db);
-                Clip4 o;
-                o.x = fmaf(tt, b.x - a.x, a.x);
-                o.y = fmaf(tt, b.y - a.y, a.y);
-                o.z = fmaf(tt, b.z - a.z, a.z);
-                o.w = fmaf(tt, b.w - a.w, a.w);
-                px[cur ^ 1][m++] = o;
+        if (active) {
+            int m = 0;
+            auto put = [&](const Clip4& q) {
+                if (m < kMaxPoly) {
+                    if (last) {
+                        bool unused;
+                        uint32_t xy;
+                        float iw;
+                        ok = project(q, fp, xy, iw, unused) && ok;
+                        pxy[m] = xy;
+                        piw[m] = iw;
+                    } else {
+                        px[cur ^ 1][m] = q;
+                    }
+                    ++m;
+                }
+            };
+            auto step = [&](const Clip4& v, Clip4& prev, float& dprev) {
+                const float dv = dist(v);
+                const bool cin = dv >= 0.0f, pin = dprev >= 0.0f;
+                if (cin != pin) {
+                    // always from the inside vertex a to the outside vertex b
+                    const Clip4 a = cin ? v : prev, b = cin ? prev : v;
+                    const float da = cin ? dv : dprev, db = cin ? dprev : dv;
+                    const float tt = da / (da - db);
+                    Clip4 o;
+                    o.x = fmaf(tt, b.x - a.x, a.x);
+                    o.y = fmaf(tt, b.y - a.y, a.y);
+                    o.z = fmaf(tt, b.z - a.z, a.z);
+                    o.w = fmaf(tt, b.w - a.w, a.w);
+                    put(o);
+                }
+                if (cin) put(v);
+                prev = v;
+                dprev = dv;
+            };
+            if (first_pass) {
+                Clip4 prev = tri[2];
+                float dprev = dist(prev);
+                step(tri[0], prev, dprev);
+                step(tri[1], prev, dprev);
+                step(tri[2], prev, dprev);
+            } else {
+                Clip4 prev = px[cur][cnt - 1];
+                float dprev = dist(prev);
+                Clip4 ahead = px[cur][0];            // fetch one vertex ahead of its use
+                for (int i = 0; i < cnt; ++i) {
+                    const Clip4 v = ahead;
+                    ahead = px[cur][min(i + 1, kMaxPoly - 1)];
+                    step(v, prev, dprev);
+                }
             }
-            if (cin && m < kMaxPoly) px[cur ^ 1][m++] = v;
-            prev = v;
-            dprev = dv;
+            cnt = m;
+            cur ^= 1;
+            if (cnt < 3) todo = 0u;
         }
-        cnt = m;
-        cur ^= 1;
-        if (cnt < 3) todo = 0u;
+        first_pass = false;
     }
-    if (cnt < 3) cnt = 0;
-    // project every polygon vertex; one failure drops the triangle
-    uint32_t pxy[kMaxPoly];
-    float piw[kMaxPoly];
-    bool ok = true;
-    for (int i = 0; i < cnt; i += 2) {      // two vertices per step: both fetches are in flight together
-        const Clip4 q0 = px[cur][i], q1 = px[cur][min(i + 1, kMaxPoly - 1)];
-        bool unused;
-        uint32_t xy0, xy1;
-        float iw0, iw1;
-        ok = project(q0, fp, xy0, iw0, unused) && ok;
-        pxy[i] = xy0; piw[i] = iw0;
-        if (i + 1 < cnt) {
-            ok = project(q1, fp, xy1, iw1, unused) && ok;
-            pxy[i + 1] = xy1; piw[i + 1] = iw1;
-        }
-    }
-    if (!ok) cnt = 0;
+    if (cnt < 3 || !ok) cnt = 0;
     const BPS_GLOBAL uint32_t* ctri_id = gptr(sc.ctri_id);
     const uint32_t tri_ref = c * 128u + slot;
     // fan (0, i, i + 1): vertex i is the previous piece's last one, and the next one is fetched ahead
