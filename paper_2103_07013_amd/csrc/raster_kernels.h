@@ -81,8 +81,8 @@ __host__ __device__ inline size_t lds_bytes(int tile_h, int tile_w, int threads,
 
 // DIAG = true is the instance launched while diagnostics are on; it alone keeps counters and timers.
 // CULL = FrameParams::cull of the launch (0 none, 1 frustum, 2 frustum + occlusion).
-// WHOLE64 = the frame is 64x64 and one window.
-template <int NT, bool DIAG, int CULL, bool WHOLE64>
+// FRAME = 64 or 128: the frame is square of that size and drawn as 64x64 windows; 0 = any frame.
+template <int NT, bool DIAG, int CULL, int FRAME>
 __global__ void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                          const float* __restrict__ view_proj, FrameParams fp, unsigned long long* __restrict__ gvis,
                          float* __restrict__ out_depth, uint32_t* __restrict__ out_id,

@@ -454,7 +454,7 @@ __device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool wan
 }  // namespace
 
 // =============================================================================================
-template <int NT, bool DIAG, int CULL, bool WHOLE64>
+template <int NT, bool DIAG, int CULL, int FRAME>
 __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ scenes, const WorkItem* __restrict__ items,
                                                const float* __restrict__ view_proj, FrameParams fp,
                                                unsigned long long* __restrict__ gvis, float* __restrict__ out_depth,
@@ -470,13 +470,15 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // LDS is sized for a full tile; edge tiles may be smaller.  The 64x64 instance also fixes the
     // capacity of the survivor list, so that every LDS address below is a compile-time constant.
-    FrameParams fq = fp;      // the frame parameters the loops use: constants in the 64x64 instance
-    if (WHOLE64) {
-        fq.H = 64; fq.W = 64; fq.tile_w = 64; fq.tile_h = 64;
-        fq.sx = 8192.0f; fq.sy = 8192.0f; fq.xmax = 16448.0f; fq.ymax = 16448.0f;
+    // FRAME = 64 or 128: an instance for square frames of that size, drawn as 64x64 windows (the
+    // paper's two resolutions).  The frame parameters the loops use are constants there.
+    FrameParams fq = fp;
+    if (FRAME) {
+        fq.H = FRAME; fq.W = FRAME; fq.tile_w = 64; fq.tile_h = 64;
+        fq.sx = 128.0f * FRAME; fq.sy = 128.0f * FRAME; fq.xmax = 256.0f * FRAME + 64.0f; fq.ymax = 256.0f * FRAME + 64.0f;
     }
-    const int HW = WHOLE64 ? 64 * 64 : fp.tile_w * fp.tile_h;
-    const int list_cap = WHOLE64 ? (int)kListCap64 : fp.list_cap;
+    const int HW = FRAME ? 64 * 64 : fp.tile_w * fp.tile_h;
+    const int list_cap = FRAME ? (int)kListCap64 : fp.list_cap;
 
     u64* vis = reinterpret_cast<u64*>(smem);
     unsigned char* wbase = smem + (size_t)HW * 8 + (size_t)wave * kWaveLdsBytes;
@@ -511,11 +513,16 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     // this work-group's window of the frame
     const int tiles_x = (fp.W + fp.tile_w - 1) / fp.tile_w;
     Window win;
-    if (WHOLE64) {
+    if (FRAME == 64) {
         // the instance for 64x64 frames (the paper's main resolution): the window is the frame, and
         // with its origin and size known to the compiler the pixel arithmetic of every loop shrinks
         win.x0 = 0; win.y0 = 0; win.w = 64; win.h = 64;
         win.aL = -1.0f; win.aR = 1.0f; win.aT = -1.0f; win.aB = 1.0f;
+    } else if (FRAME == 128) {
+        // 128x128 frames: four windows of known size; only the origin depends on the item
+        win.x0 = (int)(item.tile & 1u) * 64; win.y0 = (int)(item.tile >> 1) * 64; win.w = 64; win.h = 64;
+        win.aL = (float)win.x0 * (1.0f / 64.0f) - 1.0f; win.aR = win.aL + 1.0f;
+        win.aT = (float)win.y0 * (1.0f / 64.0f) - 1.0f; win.aB = win.aT + 1.0f;
     } else {
         win.x0 = (int)(item.tile % (uint32_t)tiles_x) * fp.tile_w;
         win.y0 = (int)(item.tile / (uint32_t)tiles_x) * fp.tile_h;
@@ -1120,10 +1127,10 @@ __global__ void k_fill_keys(unsigned long long* __restrict__ gvis, size_t n) {
 namespace {
 template <bool DIAG, int CULL>
 const void* raster_entry(int threads) {
-    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG, CULL, false>)
-           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG, CULL, false>)
-           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG, CULL, false>)
-                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG, CULL, false>);
+    return threads == 256   ? reinterpret_cast<const void*>(&k_raster<256, DIAG, CULL, 0>)
+           : threads == 384 ? reinterpret_cast<const void*>(&k_raster<384, DIAG, CULL, 0>)
+           : threads == 512 ? reinterpret_cast<const void*>(&k_raster<512, DIAG, CULL, 0>)
+                            : reinterpret_cast<const void*>(&k_raster<1024, DIAG, CULL, 0>);
 }
 }  // namespace
 
@@ -1134,22 +1141,31 @@ hipError_t prepare_raster(int threads, size_t lds) {
         hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_raster<512, false, 2, true>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_raster<512, false, 2, 64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_raster<512, false, 2, 128>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats) {
-    // 64x64 frames in the default configuration have an instance of their own
-    if (threads == 512 && !stats && fp.cull == 2 && fp.W == 64 && fp.H == 64 && fp.tile_w == 64 && fp.tile_h == 64 &&
-        fp.list_cap == (int)kListCap64) {
-        hipLaunchKernelGGL((k_raster<512, false, 2, true>), grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis,
-                           out_depth, out_id, stats);
-        return;
+    // 64x64 and 128x128 frames in the default configuration have instances of their own
+    if (threads == 512 && !stats && fp.cull == 2 && fp.tile_w == 64 && fp.tile_h == 64 && fp.list_cap == (int)kListCap64) {
+        if (fp.W == 64 && fp.H == 64) {
+            hipLaunchKernelGGL((k_raster<512, false, 2, 64>), grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis,
+                               out_depth, out_id, stats);
+            return;
+        }
+        if (fp.W == 128 && fp.H == 128) {
+            hipLaunchKernelGGL((k_raster<512, false, 2, 128>), grid, dim3(512), lds, stream, scenes, items, view_proj, fp, gvis,
+                               out_depth, out_id, stats);
+            return;
+        }
     }
 #define BPS_LAUNCH3(NT, DIAG, CULL)                                                                                    \
-    hipLaunchKernelGGL((k_raster<NT, DIAG, CULL, false>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,      \
+    hipLaunchKernelGGL((k_raster<NT, DIAG, CULL, 0>), grid, dim3(NT), lds, stream, scenes, items, view_proj, fp, gvis,          \
                        out_depth, out_id, stats)
 #define BPS_LAUNCH2(NT, DIAG)                                                                                          \
     do {                                                                                                               \
