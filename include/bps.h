@@ -144,8 +144,9 @@ bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
                       float *out_depth, uint8_t *out_rgb, uint32_t *out_tri_id, void *stream);
 
-/* Timing aid for benchmarks: when enabled, bps_render brackets its rasterisation kernel(s) with
- * HIP events on the caller's stream (request staging is outside the bracket).
+/* Timing aid for benchmarks: when enabled, bps_render brackets its raster kernel (the one launch
+ * of k_raster) with HIP events on the caller's stream; request staging, the two planning kernels
+ * and the resolve / colour / downsample kernels are outside the bracket.
  * bps_last_kernel_ms waits for the most recent request's events and returns its duration in
  * milliseconds.  bps_kernel_ms_total waits for every request profiled since the last call (or
  * since profiling was enabled; at most 4096 are remembered), returns their count and summed

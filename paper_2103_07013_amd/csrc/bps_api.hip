@@ -817,7 +817,11 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
                            16 * n_items);
         d_stats = r->d_stats;
     }
-    hipEvent_t ev_stop = nullptr;
+    if (planned) {
+        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
+        BPS_HIP(r, hipGetLastError());
+    }
+    hipEvent_t ev_stop = nullptr;      // profiling: the events bracket the raster kernel alone
     if (r->profiling && r->ev_used + 2 <= 2 * kMaxProfiled) {
         while (r->ev.size() < r->ev_used + 2) {
             hipEvent_t e;
@@ -828,13 +832,10 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         ev_stop = r->ev[r->ev_used + 1];
         r->ev_used += 2;
     }
-    if (planned) {
-        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
-        BPS_HIP(r, hipGetLastError());
-    }
     bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, planned ? d_ordered : d_items, d_vp, fp,
                        r->gvis, out_depth, out_tri_id, d_stats);
     BPS_HIP(r, hipGetLastError());
+    if (ev_stop) BPS_HIP(r, hipEventRecord(ev_stop, stream));
     if (S > 1) {
         size_t n = (size_t)B * HW;
         hipLaunchKernelGGL(bps::k_resolve, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, r->gvis, n, fp.background,
@@ -849,7 +850,6 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         bps::launch_downsample(stream, out_depth, out_rgb, B, H, W, final_depth, final_rgb);
         BPS_HIP(r, hipGetLastError());
     }
-    if (ev_stop) BPS_HIP(r, hipEventRecord(ev_stop, stream));
     BPS_HIP(r, hipEventRecord(slot.done, stream));
     slot.pending = true;
     slot.seq = seq;
