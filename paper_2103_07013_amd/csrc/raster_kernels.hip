@@ -633,7 +633,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 break;
             }
             const uint32_t jb = sorted ? (uint32_t)order[blk] : blk;
-            if (occlusion && jb == 0xFFFFu) {      // struck out: the whole block is hidden
+            if (occlusion && sorted && jb == 0xFFFFu) {      // struck out: the whole block is hidden
                 if (lane == 0) atomicSub(reserved, 64u);
                 continue;
             }

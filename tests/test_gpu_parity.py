@@ -342,3 +342,18 @@ def test_connected_scene_under_arbitrary_cameras(seed, H, W):
         gd, gi, _ = _render_gpu([scene], [0] * 16, Ms, H, W, flags=flags)
         _compare(gd, gi, ref, f"seed {seed} {H}x{W} flags={flags}")
     assert (ref["tri_id"] != NOHIT).mean() > 0.3
+
+
+def test_scene_with_more_blocks_than_the_visiting_order_holds():
+    """A 6.3 M-triangle scene has 1032 blocks of 64 clusters, more than a work-group can rank near to
+    far (1024): with one work-group per environment the blocks are then visited in storage order and
+    none may be skipped; split over several work-groups each share is small enough to be ranked."""
+    import oracle
+    scene = synth.make_multiroom_scene(6_300_000, seed=1700)
+    cams = synth.make_cameras(scene, 4, seed=9)[0]
+    ref = oracle.render_scene(scene.vertices, scene.indices, cams, 64, 64)
+    for splits in (1, 0):
+        gd, gi, info = _render_gpu([scene], [0] * 4, cams, 64, 64, splits=splits)
+        if splits == 1:
+            assert info["groups"] == 4
+        _compare(gd, gi, ref, f"splits={splits}")
