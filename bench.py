@@ -100,6 +100,28 @@ def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=
     return res
 
 
+def inputs_ready_run(bps, torch, w, steps, warmup):
+    """The headline request with BPS_FLAG_INPUTS_READY: the matrices, resident on the device since before
+    the timed region, are declared complete at every call, so the renderer stages and plans each
+    request on its own stream while the previous one is still being drawn."""
+    r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, flags=bps.FLAG_INPUTS_READY)
+    handles = [r.load_scene(s.vertices, s.indices) for s in w.scenes]
+    ids = np.array([handles[k] for k in w.scene_ids], np.int32)
+    vp = torch.from_numpy(w.view_proj).cuda()
+    depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    r.close()
+    return {"value": w.B * steps / dt, "unit": "frames/s", "steps": steps, "ms_per_step": dt * 1e3 / steps}
+
+
 def in_flight_run(bps, torch, w, steps, warmup, n_streams=2):
     """The same requests issued alternately on n_streams streams, each with its own output frames,
     so that consecutive requests overlap on the device and fill the compute units that the end of
@@ -210,6 +232,9 @@ def main():
     ap.add_argument("--no-cull", action="store_true", help="stream every cluster (no culling of clusters)")
     ap.add_argument("--no-occlusion", action="store_true", help="frustum culling of clusters only")
     ap.add_argument("--no-dispatch-order", action="store_true", help="launch work-groups in batch order")
+    ap.add_argument("--inputs-ready", action="store_true",
+                    help="tell the renderer that the device-resident matrices are complete at every call, so that it plans "
+                         "the launch on its own stream while the previous request is still being drawn")
     ap.add_argument("--sweep", action="store_true", help="batch-size x resolution sweep instead of the single benchmark line")
     ap.add_argument("--textured", action="store_true",
                     help="RGB-D workloads: colour from each scene's texture (uv + mip pyramid) instead of vertex colours")
@@ -249,7 +274,8 @@ def main():
         return
     w = synth.build_config(args.config, B=args.batch)
     flags = ((bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0) | (bps.FLAG_NO_OCCLUSION_CULL if args.no_occlusion else 0) |
-             (bps.FLAG_NO_DISPATCH_ORDER if args.no_dispatch_order else 0))
+             (bps.FLAG_NO_DISPATCH_ORDER if args.no_dispatch_order else 0) |
+             (bps.FLAG_INPUTS_READY if args.inputs_ready else 0))
     culling = not args.no_cull
     main_run = timed_run(bps, torch, w, flags, args.steps, args.warmup, args.splits, args.threads,
                          diagnostics=culling and not args.no_extras, textured=args.textured)
@@ -361,6 +387,8 @@ def main():
         out["roofline_full_stream"] = rl
     if culling and not args.no_extras and not w.rgbd and args.splits <= 1:
         out["two_requests_in_flight"] = in_flight_run(bps, torch, w, args.steps, args.warmup)
+        if not args.inputs_ready:
+            out["inputs_declared_ready"] = inputs_ready_run(bps, torch, w, args.steps, args.warmup)
     if args.rotate and not w.rgbd:
         out["rotation"] = rotation_run(bps, torch, w, max(2000, args.steps), args.warmup)
     if args.cpu_envs > 0:

@@ -51,7 +51,12 @@ enum { BPS_MODE_DEPTH = 0, BPS_MODE_RGBD = 1 };
 enum {
     BPS_FLAG_NO_CLUSTER_CULL = 1,   /* stream every cluster of the scene for every environment */
     BPS_FLAG_NO_OCCLUSION_CULL = 2, /* frustum culling only: do not skip clusters hidden behind nearer geometry */
-    BPS_FLAG_NO_DISPATCH_ORDER = 4  /* launch work-groups in batch order instead of costliest first */
+    BPS_FLAG_NO_DISPATCH_ORDER = 4, /* launch work-groups in batch order instead of costliest first */
+    BPS_FLAG_INPUTS_READY = 8       /* the caller vouches that device-resident view_proj arrays are complete
+                                       when bps_render is called (no pending work on any stream still writes
+                                       them): staging and launch planning may then start at once, on a stream
+                                       of the renderer, instead of queuing behind the caller's stream.  Host
+                                       arrays are consumed during the call and always get this treatment. */
 };
 
 typedef struct {

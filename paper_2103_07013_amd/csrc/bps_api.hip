@@ -60,6 +60,7 @@ struct RingSlot {
     unsigned char* dev = nullptr;
     size_t capacity = 0;
     hipEvent_t done = nullptr;
+    hipEvent_t planned = nullptr;    // launch plan ready (only used when planning runs on the renderer's own stream)
     bool pending = false;
     uint64_t seq = 0;
     uint64_t items_version = 0;      // plan whose work items the device buffer holds (0 = none)
@@ -86,6 +87,7 @@ struct bps_renderer {
     std::vector<Arena> arena_pool;    // free device blocks, reused by later loads
     std::vector<Staging> staging;     // pinned images, reused once their copy has finished
     hipStream_t load_stream = nullptr;   // used by the synchronous bps_load_scene
+    hipStream_t plan_stream = nullptr;   // staging + launch planning of requests whose inputs are complete at the call
     uint64_t seq = 0, done_seq = 0;   // requests issued / known complete
     uint64_t arena_allocs = 0;        // device blocks allocated so far (reuse keeps this flat)
     std::mutex mu;                    // guards all state: one loader thread may run beside the render thread
@@ -206,7 +208,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
     if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 384 && cfg->threads != 512 && cfg->threads != 1024)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 384, 512 or 1024");
     if (cfg->splits < 0) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be >= 0");
-    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL | BPS_FLAG_NO_DISPATCH_ORDER)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
+    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL | BPS_FLAG_NO_DISPATCH_ORDER | BPS_FLAG_INPUTS_READY)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
         return fail(nullptr, BPS_ERR_HIP, "bps_create: no HIP device available (this library has no CPU path)");
@@ -274,8 +276,12 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
         BPS_HIP(r, hipMemset(r->d_scenes, 0, sizeof(bps::SceneDev) * kMaxScenes));
-        for (RingSlot& s : r->ring) BPS_HIP(r, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+        for (RingSlot& s : r->ring) {
+            BPS_HIP(r, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+            BPS_HIP(r, hipEventCreateWithFlags(&s.planned, hipEventDisableTiming));
+        }
         BPS_HIP(r, hipStreamCreateWithFlags(&r->load_stream, hipStreamNonBlocking));
+        BPS_HIP(r, hipStreamCreateWithFlags(&r->plan_stream, hipStreamNonBlocking));
         return BPS_OK;
     };
     st = step();
@@ -297,10 +303,12 @@ void bps_destroy(bps_renderer* r) {
         (void)hipEventDestroy(x.done);
     }
     if (r->load_stream) (void)hipStreamDestroy(r->load_stream);
+    if (r->plan_stream) (void)hipStreamDestroy(r->plan_stream);
     for (RingSlot& s : r->ring) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.dev) (void)hipFree(s.dev);
         if (s.done) (void)hipEventDestroy(s.done);
+        if (s.planned) (void)hipEventDestroy(s.planned);
     }
     if (r->gvis) (void)hipFree(r->gvis);
     if (r->ids) (void)hipFree(r->ids);
@@ -645,6 +653,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     }
     BPS_HIP(r, hipSetDevice(r->device));
     const uint64_t seq = ++r->seq;
+    std::vector<hipEvent_t> uploads_pending;      // asynchronous scene uploads this request has to follow
     for (uint32_t b = 0; b < B; ++b) {
         HostScene& hs = r->scenes[scene_ids[b]];
         if (hs.last_use == seq) continue;     // already handled for this request
@@ -656,6 +665,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
             } else {
                 (void)hipGetLastError();
                 BPS_HIP(r, hipStreamWaitEvent(stream, hs.ready, 0));
+                uploads_pending.push_back(hs.ready);
             }
         }
     }
@@ -756,8 +766,16 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         std::memcpy(slot.host + items_bytes + ids_bytes, view_proj, vp_bytes);
         copy_to = items_bytes + ids_bytes + vp_bytes;
     }
+    // Staging and launch planning read nothing but the request.  When the request is complete at the
+    // call (host matrices, or device matrices the caller vouches for), they run on the renderer's own
+    // stream and may start while the caller's stream is still busy with earlier work: the planning
+    // kernels then fill the compute units that the end of the previous request's launch leaves idle.
+    const bool early = planned && (!vp_on_device || (r->cfg.flags & BPS_FLAG_INPUTS_READY));
+    hipStream_t pstream = early ? r->plan_stream : stream;
+    if (early)
+        for (hipEvent_t e : uploads_pending) BPS_HIP(r, hipStreamWaitEvent(pstream, e, 0));
     if (copy_to > copy_from)
-        BPS_HIP(r, hipMemcpyAsync(payload + copy_from, slot.host + copy_from, copy_to - copy_from, hipMemcpyHostToDevice, stream));
+        BPS_HIP(r, hipMemcpyAsync(payload + copy_from, slot.host + copy_from, copy_to - copy_from, hipMemcpyHostToDevice, pstream));
     slot.items_version = r->plan_version;
     const bps::WorkItem* d_items = reinterpret_cast<const bps::WorkItem*>(payload);
     const uint32_t* d_env_scene = reinterpret_cast<const uint32_t*>(payload + items_bytes);
@@ -818,8 +836,12 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         d_stats = r->d_stats;
     }
     if (planned) {
-        bps::launch_plan(stream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
+        bps::launch_plan(pstream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
         BPS_HIP(r, hipGetLastError());
+        if (early) {
+            BPS_HIP(r, hipEventRecord(slot.planned, pstream));
+            BPS_HIP(r, hipStreamWaitEvent(stream, slot.planned, 0));
+        }
     }
     hipEvent_t ev_stop = nullptr;      // profiling: the events bracket the raster kernel alone
     if (r->profiling && r->ev_used + 2 <= 2 * kMaxProfiled) {

@@ -218,3 +218,36 @@ def test_requests_in_flight_on_two_streams(rgbd):
             assert np.array_equal(depth.cpu().numpy(), refs[k]["depth"][:n]), f"request {step}"
             if rgbd:
                 assert np.array_equal(rgb.cpu().numpy(), refs[k]["rgb"][:n]), f"request {step}"
+
+
+@pytest.mark.parametrize("device_matrices", [False, True])
+def test_requests_planned_on_the_renderers_own_stream(device_matrices):
+    """Requests whose inputs are complete at the call (host matrices always; device matrices with
+    FLAG_INPUTS_READY) are staged and planned on a stream of the renderer while earlier requests are
+    still being drawn.  Batches large enough for launch planning, different cameras and batch sizes
+    back to back, a scene uploaded asynchronously in between: every frame must match the oracle."""
+    import torch
+    import oracle
+    import paper_2103_07013_amd as bps
+    scenes = [synth.make_multiroom_scene(30_000, seed=1800 + k) for k in range(2)]
+    B = 640                                                  # more work-groups than the device holds at once
+    cams = [synth.make_cameras(sc, B, seed=31 + k)[0] for k, sc in enumerate(scenes)]
+    refs = [oracle.render_scene(sc.vertices, sc.indices, cams[k], 64, 64) for k, sc in enumerate(scenes)]
+    copy_stream = torch.cuda.Stream()
+    with bps.Renderer(max_batch=B, flags=bps.FLAG_INPUTS_READY if device_matrices else 0) as r:
+        h0 = r.load_scene(scenes[0].vertices, scenes[0].indices)
+        h1 = None
+        outs = []
+        mats = [torch.from_numpy(c).cuda() if device_matrices else c for c in cams]
+        torch.cuda.synchronize()                             # the device matrices are complete from here on
+        for step in range(8):
+            if step == 3:
+                h1 = r.load_scene_async(scenes[1].vertices, scenes[1].indices, copy_stream=copy_stream)
+            k = 1 if (h1 is not None and step % 2 == 1) else 0
+            n = B - 37 * (step % 3)
+            depth = torch.empty((n, 64, 64), dtype=torch.float32, device="cuda")
+            bps.bps_render(r.handle, np.full(n, h1 if k else h0, np.int32), mats[k][:n], depth)
+            outs.append((k, n, depth))
+        torch.cuda.synchronize()
+        for step, (k, n, depth) in enumerate(outs):
+            assert np.array_equal(depth.cpu().numpy(), refs[k]["depth"][:n]), f"request {step}"
