@@ -281,7 +281,6 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
             BPS_HIP(r, hipEventCreateWithFlags(&s.planned, hipEventDisableTiming));
         }
         BPS_HIP(r, hipStreamCreateWithFlags(&r->load_stream, hipStreamNonBlocking));
-        BPS_HIP(r, hipStreamCreateWithFlags(&r->plan_stream, hipStreamNonBlocking));
         return BPS_OK;
     };
     st = step();
@@ -771,6 +770,9 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     // stream and may start while the caller's stream is still busy with earlier work: the planning
     // kernels then fill the compute units that the end of the previous request's launch leaves idle.
     const bool early = planned && (!vp_on_device || (r->cfg.flags & BPS_FLAG_INPUTS_READY));
+    // (the stream is made on first use: the device has few hardware queues, and a stream nobody uses
+    // could take the one that lets two caller streams run side by side)
+    if (early && !r->plan_stream) BPS_HIP(r, hipStreamCreateWithFlags(&r->plan_stream, hipStreamNonBlocking));
     hipStream_t pstream = early ? r->plan_stream : stream;
     if (early)
         for (hipEvent_t e : uploads_pending) BPS_HIP(r, hipStreamWaitEvent(pstream, e, 0));
