@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+PROFILE_EVERY = 4               # the events cost ~6 us per request: time a quarter of the launches
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4      # wave64 vector instructions per second: 256 CUs x 4 SIMDs, 4 cycles each
 
 
@@ -61,7 +62,8 @@ def measured_traffic(key):
         return None
 
 
-def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False, textured=False):
+def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False, textured=False,
+              profile_every=1):
     mode = bps.MODE_RGBD if w.rgbd else bps.MODE_DEPTH
     r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, mode=mode, splits=splits, threads=threads, flags=flags)
     if textured and w.rgbd:
@@ -76,7 +78,7 @@ def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=
     for _ in range(warmup):
         bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
     torch.cuda.synchronize()
-    bps.bps_set_profiling(r.handle, True)
+    bps.bps_set_profiling(r.handle, profile_every)       # HIP events around every n-th raster launch of the timed region
     t0 = time.perf_counter()
     for _ in range(steps):
         bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
@@ -278,7 +280,8 @@ def main():
              (bps.FLAG_INPUTS_READY if args.inputs_ready else 0))
     culling = not args.no_cull
     main_run = timed_run(bps, torch, w, flags, args.steps, args.warmup, args.splits, args.threads,
-                         diagnostics=culling and not args.no_extras, textured=args.textured)
+                         diagnostics=culling and not args.no_extras, textured=args.textured,
+                         profile_every=PROFILE_EVERY if args.steps >= 80 else 1)
     dt = main_run["dt"]
     kernel_ms_avg = main_run["kernel_ms_avg"]
     variant = "full_stream" if args.no_cull else ("frustum_cull" if args.no_occlusion else "cull")

@@ -151,7 +151,9 @@ bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *
 
 /* Timing aid for benchmarks: when enabled, bps_render brackets its raster kernel (the one launch
  * of k_raster) with HIP events on the caller's stream; request staging, the two planning kernels
- * and the resolve / colour / downsample kernels are outside the bracket.
+ * and the resolve / colour / downsample kernels are outside the bracket.  enable = 1 times every
+ * request, enable = n > 1 every n-th one (the first, the (n+1)-th, ...: the events themselves cost a
+ * few microseconds per request), 0 switches it off.
  * bps_last_kernel_ms waits for the most recent request's events and returns its duration in
  * milliseconds.  bps_kernel_ms_total waits for every request profiled since the last call (or
  * since profiling was enabled; at most 4096 are remembered), returns their count and summed

@@ -214,7 +214,8 @@ def bps_render(handle, scene_ids, view_proj, out_depth, out_rgb=None, out_tri_id
 
 
 def bps_set_profiling(handle, enable=True):
-    _check(load_library().bps_set_profiling(handle, 1 if enable else 0), handle)
+    """enable: False / 0 = off, True / 1 = time every request, n > 1 = time every n-th request."""
+    _check(load_library().bps_set_profiling(handle, int(enable)), handle)
 
 
 def bps_last_kernel_ms(handle):

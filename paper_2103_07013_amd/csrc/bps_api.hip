@@ -102,6 +102,7 @@ struct bps_renderer {
     std::vector<hipEvent_t> ev;           // profiling: pairs (start, stop), one pair per request
     size_t ev_used = 0;
     bool profiling = false;
+    uint32_t profile_every = 1, profile_count = 0;   // every n-th request is timed
     // cached plan: valid while the scene ids and split count repeat
     std::vector<bps_scene> plan_ids;
     int plan_splits = 0;
@@ -846,7 +847,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         }
     }
     hipEvent_t ev_stop = nullptr;      // profiling: the events bracket the raster kernel alone
-    if (r->profiling && r->ev_used + 2 <= 2 * kMaxProfiled) {
+    if (r->profiling && (r->profile_count++ % r->profile_every) == 0 && r->ev_used + 2 <= 2 * kMaxProfiled) {
         while (r->ev.size() < r->ev_used + 2) {
             hipEvent_t e;
             BPS_HIP(r, hipEventCreate(&e));
@@ -889,6 +890,8 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
 bps_status bps_set_profiling(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
     r->profiling = enable != 0;
+    r->profile_every = enable > 1 ? (uint32_t)enable : 1u;
+    r->profile_count = 0;
     r->ev_used = 0;
     return BPS_OK;
 }
