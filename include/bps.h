@@ -144,7 +144,7 @@ bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
  * buffers must stay alive until the stream reaches the end of the request.
  * Requests on one stream run in order.  Requests on different streams may overlap on the device
  * (two requests in flight fill the compute units that the end of a launch leaves idle); the library
- * itself orders those that use its internal buffers (RGB-D without out_tri_id, split frames,
+ * itself orders those that use its internal buffers (RGB-D requests, split frames,
  * supersampling, diagnostics). */
 bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
                       float *out_depth, uint8_t *out_rgb, uint32_t *out_tri_id, void *stream);

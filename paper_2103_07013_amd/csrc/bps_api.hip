@@ -96,6 +96,8 @@ struct bps_renderer {
     int ring_next = 0;
     unsigned long long* gvis = nullptr;   // [max_batch][H][W], only for split frames
     uint32_t* ids = nullptr;              // [max_batch][H][W], RGB-D requests without a caller id buffer
+    uint32_t* shade_queue = nullptr;      // queues of the pixels whose winner needs the clipper, then two counter blocks
+    uint32_t shade_parity = 0;            // which of the two counters the next RGB-D request uses
     unsigned long long* d_stats = nullptr;   // diagnostics block: 8 counters + one duration per work-group
     size_t stats_cap = 0;
     bool want_stats = false, want_phase_timers = false;
@@ -312,6 +314,7 @@ void bps_destroy(bps_renderer* r) {
     }
     if (r->gvis) (void)hipFree(r->gvis);
     if (r->ids) (void)hipFree(r->ids);
+    if (r->shade_queue) (void)hipFree(r->shade_queue);
     if (r->ss_depth) (void)hipFree(r->ss_depth);
     if (r->ss_rgb) (void)hipFree(r->ss_rgb);
     if (r->d_stats) (void)hipFree(r->d_stats);
@@ -374,7 +377,12 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
             if (a_ == 1 && b_ == 1) break;
         }
     const size_t o_uv = textured ? place((size_t)V * 8) : 0, o_tex = textured ? place(pyramid_texels * 4) : 0;
+    const size_t copy_bytes = off;      // what the pinned image holds and the upload copies
+    // per-triangle shading records (64 B each), built on the device from the uploaded arrays
+    const bool shaded = colors != nullptr || textured;
+    const size_t o_trirec = shaded ? place((size_t)T * 64) : 0;
     const size_t dev_bytes = off;
+    off = copy_bytes;
     const size_t o_rec = place(sizeof(bps::SceneDev));
     const size_t img_bytes = off;
 
@@ -498,6 +506,7 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
     hs.dev.tex_w = textured ? tex.w : 0;
     hs.dev.tex_h = textured ? tex.h : 0;
     hs.dev.tex_levels = tex_levels;
+    hs.dev.tri_rec = shaded ? (const float*)(d + o_trirec) : nullptr;
     hs.dev.cbounds = (const float*)(d + o_cb);
     hs.dev.bbounds = (const float*)(d + o_bb);
     hs.dev.n_clusters = cs.count;
@@ -513,8 +522,13 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
         (void)hipEventRecord(stg.done, stream);
         return fail(r, BPS_ERR_HIP, "bps_load_scene: %s: %s", what, hipGetErrorString(e));
     };
-    hipError_t e = hipMemcpyAsync(d, img, dev_bytes, hipMemcpyHostToDevice, stream);
+    hipError_t e = hipMemcpyAsync(d, img, copy_bytes, hipMemcpyHostToDevice, stream);
     if (e != hipSuccess) return undo(e, "mesh copy");
+    if (shaded) {
+        bps::launch_build_shade_records(stream, hs.dev, (float*)(d + o_trirec));
+        e = hipGetLastError();
+        if (e != hipSuccess) return undo(e, "shading records");
+    }
     e = hipMemcpyAsync(r->d_scenes + slot, img + o_rec, sizeof(bps::SceneDev), hipMemcpyHostToDevice, stream);
     if (e != hipSuccess) return undo(e, "scene table update");
     e = hipEventCreateWithFlags(&hs.ready, hipEventDisableTiming);
@@ -805,7 +819,13 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
 
     // Requests on one stream run in order.  A request on another stream may overlap the previous one
     // unless both use one of the renderer's own buffers: then it waits for that one.
-    const bool uses_shared = (rgbd && out_tri_id == r->ids) || S > 1 || r->ss > 1 || r->want_stats;
+    // ---- RGB-D: queue of the pixels whose winning triangle crosses a clip plane, and its two counters
+    if (rgbd && !r->shade_queue) {
+        const size_t n = (size_t)bps::kShadeQueues * bps::shade_queue_cap((size_t)r->cfg.max_batch * HW);
+        BPS_HIP(r, hipMalloc((void**)&r->shade_queue, (n + 2 * 32 * bps::kShadeQueues) * sizeof(uint32_t)));
+        BPS_HIP(r, hipMemsetAsync(r->shade_queue + n, 0, 2 * 32 * bps::kShadeQueues * sizeof(uint32_t), stream));
+    }
+    const bool uses_shared = rgbd || S > 1 || r->ss > 1 || r->want_stats;
     if (uses_shared && r->shared_done && r->shared_stream != stream) BPS_HIP(r, hipStreamWaitEvent(stream, r->shared_done, 0));
 
     bps::FrameParams fp;
@@ -868,7 +888,11 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         BPS_HIP(r, hipGetLastError());
     }
     if (rgbd) {
-        bps::launch_shade(stream, r->d_scenes, d_env_scene, d_vp, fp, B, out_tri_id, out_rgb);
+        uint32_t* counters = r->shade_queue + (size_t)bps::kShadeQueues * bps::shade_queue_cap((size_t)r->cfg.max_batch * HW);
+        bps::launch_shade(stream, r->d_scenes, d_env_scene, d_vp, fp, B, out_tri_id, out_rgb, r->shade_queue,
+                          counters + 32 * bps::kShadeQueues * r->shade_parity,
+                          counters + 32 * bps::kShadeQueues * (r->shade_parity ^ 1u));
+        r->shade_parity ^= 1u;
         BPS_HIP(r, hipGetLastError());
     }
     if (r->ss > 1) {

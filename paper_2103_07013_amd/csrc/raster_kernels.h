@@ -33,6 +33,8 @@ struct SceneDev {
     const uint8_t* colors;     // [V][3] or null
     const float* uvs;          // [V][2] or null (textured scenes)
     const uint32_t* texels;    // RGBA8 mip pyramid, level after level, or null
+    const float* tri_rec;      // [T][16]    per-triangle shading record (scenes with colours or a texture), or null:
+                               //            x0 y0 z0 x1 y1 z1 x2 y2 z2, then three packed RGB words or u0 v0 u1 v1 u2 v2
     uint32_t tex_w, tex_h, tex_levels, pad2;
     uint32_t n_clusters, n_tris, n_verts, c_stride, b_stride, pad;
 };
@@ -105,7 +107,19 @@ void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* ite
 hipError_t prepare_raster(int threads, size_t lds);
 void launch_downsample(hipStream_t stream, const float* depth, const uint8_t* rgb, uint32_t B, int H, int W,
                        float* out_depth, uint8_t* out_rgb);
+// Colour pass.  Pixels whose winning triangle needs the clipper go through kShadeQueues queues (work-group g
+// of the first kernel appends to queue g % kShadeQueues); shade_queue_cap(pixels) words per queue hold the
+// worst case.  queue: kShadeQueues * shade_queue_cap(pixels) words; count / next_count: this request's
+// counters (32 * kShadeQueues words, all zero) and the next request's (cleared by the launch).
+constexpr uint32_t kShadeQueues = 64;
+inline uint32_t shade_queue_cap(size_t pixels) {
+    const size_t groups = (pixels + 255) / 256;
+    return (uint32_t)((groups + kShadeQueues - 1) / kShadeQueues * 256);
+}
+// Fills sc.tri_rec from the scene's original arrays (once per scene, on the stream that uploads it).
+void launch_build_shade_records(hipStream_t stream, const SceneDev& sc, float* tri_rec);
 void launch_shade(hipStream_t stream, const SceneDev* scenes, const uint32_t* env_scene, const float* view_proj,
-                  const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb);
+                  const FrameParams& fp, uint32_t B, const uint32_t* tri_id, uint8_t* out_rgb, uint32_t* queue,
+                  uint32_t* count, uint32_t* next_count);
 
 }  // namespace bps
