@@ -149,6 +149,22 @@ bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
                       float *out_depth, uint8_t *out_rgb, uint32_t *out_tri_id, void *stream);
 
+/* bps_render for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It calls no hipMalloc / hipFree / hipHostMalloc and copies nothing
+ * from host memory: the work items travel as kernel arguments, and the launch plan (work items, cost
+ * and order words) lives in a file-scope __device__ array of the library, 640 KiB on every GPU the
+ * library runs on, held until the process ends.  Same frames as bps_render, bit for bit.
+ * Limits: depth renderers without supersampling, forced splits or diagnostics; view_proj must be
+ * DEVICE memory; B x (64x64-pixel tiles per frame) <= 16384 work-groups (e.g. 16384 environments at
+ * 64x64, 4096 at 128x128), otherwise BPS_ERR_INVALID_ARG / BPS_ERR_UNSUPPORTED and nothing is enqueued.
+ * One environment is never split over several work-groups here, so very small batches run slower
+ * than through bps_render.  scene_ids is host memory as in bps_render.
+ * Every call on a GPU, from any renderer and stream, uses that GPU's one array: calls on one stream
+ * are ordered and safe; calls that overlap on one GPU (different streams or renderers) race.  Nothing
+ * in the array needs clearing: each call overwrites what it reads. */
+bps_status bps_render_static(bps_renderer *r, const bps_scene *scene_ids, const float *view_proj, uint32_t B,
+                             float *out_depth, uint32_t *out_tri_id, void *stream);
+
 /* Timing aid for benchmarks: when enabled, bps_render brackets its raster kernel (the one launch
  * of k_raster) with HIP events on the caller's stream; request staging, the two planning kernels
  * and the resolve / colour / downsample kernels are outside the bracket.  enable = 1 times every

@@ -13,7 +13,7 @@ FLAG_NO_CLUSTER_CULL = 1
 FLAG_NO_OCCLUSION_CULL = 2
 FLAG_NO_DISPATCH_ORDER = 4
 FLAG_INPUTS_READY = 8
-EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_load_scene_textured", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_set_profiling",
+EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_load_scene_textured", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_render_static", "bps_set_profiling",
            "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_kernel_ms_each", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 
 
@@ -60,6 +60,8 @@ def load_library():
     lib.bps_unload_scene.argtypes = [vp, ctypes.c_int32]
     lib.bps_render.restype = ctypes.c_int32
     lib.bps_render.argtypes = [vp, vp, vp, ctypes.c_uint32, vp, vp, vp, vp]
+    lib.bps_render_static.restype = ctypes.c_int32
+    lib.bps_render_static.argtypes = [vp, vp, vp, ctypes.c_uint32, vp, vp, vp]
     lib.bps_set_profiling.restype = ctypes.c_int32
     lib.bps_set_profiling.argtypes = [vp, ctypes.c_int32]
     lib.bps_last_kernel_ms.restype = ctypes.c_int32
@@ -211,6 +213,30 @@ def bps_render(handle, scene_ids, view_proj, out_depth, out_rgb=None, out_tri_id
     else:
         s = stream.cuda_stream
     _check(lib.bps_render(handle, ids.ctypes.data, vp_ptr, B, d_ptr, rgb_ptr, id_ptr, ctypes.c_void_p(s)), handle)
+
+
+def bps_render_static(handle, scene_ids, view_proj, out_depth, out_tri_id=None, stream=None):
+    """bps_render without any allocation: scene_ids host int32 [B]; view_proj a CUDA float32 tensor [B,4,4];
+    out_depth / out_tri_id CUDA tensors [B,H,W]; stream as in bps_render."""
+    import torch
+    lib = load_library()
+    ids = np.ascontiguousarray(scene_ids, np.int32).reshape(-1)
+    B = ids.shape[0]
+    if not isinstance(view_proj, torch.Tensor) or not view_proj.is_cuda or view_proj.dtype != torch.float32 or \
+            not view_proj.is_contiguous() or view_proj.numel() != B * 16:
+        raise ValueError("view_proj must be a contiguous CUDA float32 tensor [B,4,4]")
+    hw = out_depth.shape[-2] * out_depth.shape[-1]
+    for t, ok, name in ((out_depth, (torch.float32,), "out_depth"), (out_tri_id, (torch.int32, torch.uint32), "out_tri_id")):
+        if t is not None and (not t.is_cuda or not t.is_contiguous() or t.dtype not in ok or t.numel() != B * hw):
+            raise ValueError(f"{name}: need a contiguous CUDA tensor of {B * hw} elements, dtype in {ok}")
+    if stream is None:
+        s = torch.cuda.current_stream(out_depth.device).cuda_stream
+    elif isinstance(stream, int):
+        s = stream
+    else:
+        s = stream.cuda_stream
+    _check(lib.bps_render_static(handle, ids.ctypes.data, view_proj.data_ptr(), B, out_depth.data_ptr(),
+                                 None if out_tri_id is None else out_tri_id.data_ptr(), ctypes.c_void_p(s)), handle)
 
 
 def bps_set_profiling(handle, enable=True):

@@ -26,6 +26,20 @@ constexpr size_t kMaxProfiled = 4096;   // profiled requests remembered between 
 
 thread_local std::string g_create_error = "";
 
+// ---- scratch of bps_render_static, the entry point that allocates nothing ------------------------
+// Work items as staged, work items in launch order, and one cost and one order word per item.
+constexpr uint32_t kStaticMaxItems = bps::kMaxPlannedItems;
+constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxItems * (2 * sizeof(bps::WorkItem) + 2 * sizeof(uint32_t));
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// In host code the array's name is only a stand-in: its address on each device is looked up once
+// (bps_create, with that device current) and used from then on.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+// what the array on each device holds: the renderer and plan whose work items were unpacked last
+const void* g_scratch_owner[kMaxDevices] = {};
+uint64_t g_scratch_plan[kMaxDevices] = {};
+
 // Device memory of one scene: a single allocation holding every array, so that loading is one
 // asynchronous copy and retiring a scene can hand the block to the next load.
 struct Arena {
@@ -111,6 +125,7 @@ struct bps_renderer {
     uint64_t plan_version = 0;        // counts the plans made; ring slots remember which one they hold
     std::vector<bps::WorkItem> plan_items;
     uint64_t last_splits = 0, last_groups = 0;
+    unsigned char* static_scratch = nullptr;   // this device's copy of the static scratch array (bps_render_static)
     // last request that used a buffer every request shares (ids, gvis, ss_*, d_stats): a later one on
     // another stream waits for it
     hipEvent_t shared_done = nullptr;
@@ -188,6 +203,66 @@ int plan_splits(const bps_renderer* r, uint32_t B, uint32_t min_clusters) {
     if (groups < 2 * r->num_cu) s = (want_groups + groups - 1) / groups;
     int max_s = std::max(1, (int)(min_clusters / (uint32_t)(8 * waves)));   // >= 8 clusters per wave
     return std::max(1, std::min(s, max_s));
+}
+
+// The launch plan: one work item per (environment, tile, slice of its scene's clusters);
+// environments of one scene are kept on one accelerator die so its L2 serves every re-read of that
+// scene.  Cached while the scene ids and the split count repeat.
+void make_plan(bps_renderer* r, const bps_scene* scene_ids, uint32_t B, int S) {
+    bool replan = r->plan_splits != S || r->plan_ids.size() != B || std::memcmp(r->plan_ids.data(), scene_ids, B * sizeof(bps_scene)) != 0;
+    if (replan) {
+        std::vector<uint32_t> order(B);
+        for (uint32_t b = 0; b < B; ++b) order[b] = b;
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return scene_ids[a] < scene_ids[b]; });
+        std::vector<bps::WorkItem> sorted;
+        sorted.reserve((size_t)B * S * r->tiles);
+        for (uint32_t k = 0; k < B; ++k) {
+            uint32_t b = order[k];
+            uint32_t C = r->scenes[scene_ids[b]].dev.n_clusters;
+            (void)C;
+            for (int tile = 0; tile < r->tiles; ++tile)
+                for (int s = 0; s < S; ++s) {
+                    bps::WorkItem it;
+                    it.env = b;
+                    it.scene = (uint32_t)scene_ids[b];
+                    it.split_of = ((uint32_t)S << 16) | (uint32_t)s;
+                    it.tile = (uint32_t)tile;
+                    sorted.push_back(it);
+                }
+        }
+        const size_t n = sorted.size();
+        r->plan_items.resize(n);
+        // block i runs on die i % 8: give die x the x-th contiguous chunk of the sorted list
+        size_t start = 0;
+        for (int x = 0; x < kXcds; ++x) {
+            size_t cnt = n / kXcds + ((size_t)x < n % kXcds ? 1 : 0);
+            for (size_t k = 0; k < cnt; ++k) r->plan_items[x + k * kXcds] = sorted[start + k];
+            start += cnt;
+        }
+        r->plan_ids.assign(scene_ids, scene_ids + B);
+        r->plan_splits = S;
+        ++r->plan_version;
+    }
+}
+
+bps::FrameParams frame_params(const bps_renderer* r, int S) {
+    bps::FrameParams fp;
+    fp.H = r->rh;
+    fp.W = r->rw;
+    fp.tile_w = r->tile_w;
+    fp.tile_h = r->tile_h;
+    fp.sx = 128.0f * (float)fp.W;
+    fp.sy = 128.0f * (float)fp.H;
+    fp.xmax = 2.0f * fp.sx + 64.0f;
+    fp.ymax = 2.0f * fp.sy + 64.0f;
+    fp.background = r->cfg.background_depth;
+    fp.merge = S > 1 ? 1 : 0;
+    fp.cull = (r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL) ? 0 : (r->cfg.flags & BPS_FLAG_NO_OCCLUSION_CULL) ? 1 : 2;
+    fp.list_cap = r->list_cap;
+    fp.round_target = r->round_target;
+    fp.first_round = r->first_round;
+    fp.phase_timers = (r->want_stats && r->want_phase_timers) ? 1 : 0;
+    return fp;
 }
 
 }  // namespace
@@ -284,6 +359,17 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
             BPS_HIP(r, hipEventCreateWithFlags(&s.planned, hipEventDisableTiming));
         }
         BPS_HIP(r, hipStreamCreateWithFlags(&r->load_stream, hipStreamNonBlocking));
+        {   // address of the static scratch array on this device (every device holds its own copy)
+            std::lock_guard<std::mutex> g(g_scratch_mu);
+            if (r->device < kMaxDevices) {
+                if (!g_scratch_ptr[r->device]) {
+                    void* ptr = nullptr;
+                    BPS_HIP(r, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+                    g_scratch_ptr[r->device] = ptr;
+                }
+                r->static_scratch = (unsigned char*)g_scratch_ptr[r->device];
+            }
+        }
         return BPS_OK;
     };
     st = step();
@@ -696,42 +782,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     }
     const int S = plan_splits(r, B, min_clusters);
 
-    // ---- plan: one work item per (environment, slice of its scene's clusters); environments of
-    // one scene are kept on one accelerator die so its L2 serves every re-read of that scene
-    bool replan = r->plan_splits != S || r->plan_ids.size() != B || std::memcmp(r->plan_ids.data(), scene_ids, B * sizeof(bps_scene)) != 0;
-    if (replan) {
-        std::vector<uint32_t> order(B);
-        for (uint32_t b = 0; b < B; ++b) order[b] = b;
-        std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return scene_ids[a] < scene_ids[b]; });
-        std::vector<bps::WorkItem> sorted;
-        sorted.reserve((size_t)B * S * r->tiles);
-        for (uint32_t k = 0; k < B; ++k) {
-            uint32_t b = order[k];
-            uint32_t C = r->scenes[scene_ids[b]].dev.n_clusters;
-            (void)C;
-            for (int tile = 0; tile < r->tiles; ++tile)
-                for (int s = 0; s < S; ++s) {
-                    bps::WorkItem it;
-                    it.env = b;
-                    it.scene = (uint32_t)scene_ids[b];
-                    it.split_of = ((uint32_t)S << 16) | (uint32_t)s;
-                    it.tile = (uint32_t)tile;
-                    sorted.push_back(it);
-                }
-        }
-        const size_t n = sorted.size();
-        r->plan_items.resize(n);
-        // block i runs on die i % 8: give die x the x-th contiguous chunk of the sorted list
-        size_t start = 0;
-        for (int x = 0; x < kXcds; ++x) {
-            size_t cnt = n / kXcds + ((size_t)x < n % kXcds ? 1 : 0);
-            for (size_t k = 0; k < cnt; ++k) r->plan_items[x + k * kXcds] = sorted[start + k];
-            start += cnt;
-        }
-        r->plan_ids.assign(scene_ids, scene_ids + B);
-        r->plan_splits = S;
-        ++r->plan_version;
-    }
+    make_plan(r, scene_ids, B, S);
     const size_t n_items = r->plan_items.size();
 
     // ---- stage the request (work items + matrices unless they already live on the device)
@@ -828,22 +879,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     const bool uses_shared = rgbd || S > 1 || r->ss > 1 || r->want_stats;
     if (uses_shared && r->shared_done && r->shared_stream != stream) BPS_HIP(r, hipStreamWaitEvent(stream, r->shared_done, 0));
 
-    bps::FrameParams fp;
-    fp.H = H;
-    fp.W = W;
-    fp.tile_w = r->tile_w;
-    fp.tile_h = r->tile_h;
-    fp.sx = 128.0f * (float)W;
-    fp.sy = 128.0f * (float)H;
-    fp.xmax = 2.0f * fp.sx + 64.0f;
-    fp.ymax = 2.0f * fp.sy + 64.0f;
-    fp.background = r->cfg.background_depth;
-    fp.merge = S > 1 ? 1 : 0;
-    fp.cull = (r->cfg.flags & BPS_FLAG_NO_CLUSTER_CULL) ? 0 : (r->cfg.flags & BPS_FLAG_NO_OCCLUSION_CULL) ? 1 : 2;
-    fp.list_cap = r->list_cap;
-    fp.round_target = r->round_target;
-    fp.first_round = r->first_round;
-    fp.phase_timers = (r->want_stats && r->want_phase_timers) ? 1 : 0;
+    const bps::FrameParams fp = frame_params(r, S);
 
     unsigned long long* d_stats = nullptr;
     if (r->want_stats) {
@@ -907,6 +943,96 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         r->shared_stream = stream;
     }
     r->last_splits = (uint64_t)S;
+    r->last_groups = (uint64_t)n_items;
+    return BPS_OK;
+}
+
+bps_status bps_render_static(bps_renderer* r, const bps_scene* scene_ids, const float* view_proj, uint32_t B,
+                             float* out_depth, uint32_t* out_tri_id, void* stream_) {
+    if (!r) return BPS_ERR_INVALID_ARG;
+    if (B == 0) return BPS_OK;
+    std::lock_guard<std::mutex> lock(r->mu);
+    if (!scene_ids || !view_proj || !out_depth) return fail(r, BPS_ERR_INVALID_ARG, "bps_render_static: null argument");
+    if (B > (uint32_t)r->cfg.max_batch)
+        return fail(r, BPS_ERR_INVALID_ARG, "bps_render_static: B=%u exceeds max_batch=%d", B, r->cfg.max_batch);
+    if (r->cfg.mode != BPS_MODE_DEPTH || r->ss > 1 || r->want_stats || r->cfg.splits > 1)
+        return fail(r, BPS_ERR_UNSUPPORTED,
+                    "bps_render_static: depth renderers only, without supersampling, forced splits or diagnostics");
+    const size_t n_items = (size_t)B * (size_t)r->tiles;
+    if (n_items > kStaticMaxItems || B > 0xFFFFu)
+        return fail(r, BPS_ERR_INVALID_ARG, "bps_render_static: %zu work-groups (B x tiles of the frame) exceed the static scratch (%u)",
+                    n_items, kStaticMaxItems);
+    if (!r->static_scratch) return fail(r, BPS_ERR_UNSUPPORTED, "bps_render_static: no static scratch on device %d", r->device);
+    hipPointerAttribute_t attr;
+    const bool vp_on_device = hipPointerGetAttributes(&attr, view_proj) == hipSuccess &&
+                              (attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged);
+    (void)hipGetLastError();
+    if (!vp_on_device) return fail(r, BPS_ERR_INVALID_ARG, "bps_render_static: view_proj must be device memory");
+    hipStream_t stream = (hipStream_t)stream_;
+    for (uint32_t b = 0; b < B; ++b) {
+        bps_scene s = scene_ids[b];
+        if (s < 0 || (size_t)s >= r->scenes.size() || !r->scenes[s].live)
+            return fail(r, BPS_ERR_BAD_HANDLE, "bps_render_static: scene_ids[%u]=%d is not a loaded scene", b, s);
+    }
+    BPS_HIP(r, hipSetDevice(r->device));
+    const uint64_t seq = ++r->seq;
+    for (uint32_t b = 0; b < B; ++b) {
+        HostScene& hs = r->scenes[scene_ids[b]];
+        if (hs.last_use == seq) continue;
+        hs.last_use = seq;
+        if (hs.ready) {                       // asynchronous upload: order this request after the copy
+            if (hipEventQuery(hs.ready) == hipSuccess) {
+                (void)hipEventDestroy(hs.ready);
+                hs.ready = nullptr;
+            } else {
+                (void)hipGetLastError();
+                BPS_HIP(r, hipStreamWaitEvent(stream, hs.ready, 0));
+            }
+        }
+    }
+    make_plan(r, scene_ids, B, 1);      // (host containers only; they keep their capacity between calls)
+    // a ring slot is taken for its completion event only: scene retirement tracks requests through them
+    RingSlot& slot = r->ring[r->ring_next];
+    r->ring_next = (r->ring_next + 1) % kRing;
+    if (slot.pending) {
+        BPS_HIP(r, hipEventSynchronize(slot.done));
+        slot.pending = false;
+    }
+    // layout of the static array: items as planned, items in launch order, cost words, order words
+    bps::WorkItem* d_items = reinterpret_cast<bps::WorkItem*>(r->static_scratch);
+    bps::WorkItem* d_ordered = d_items + kStaticMaxItems;
+    uint32_t* d_cost = reinterpret_cast<uint32_t*>(d_ordered + kStaticMaxItems);
+    uint32_t* d_dispatch = d_cost + kStaticMaxItems;
+    {   // the items reach the device as kernel arguments, unless the array still holds this very plan
+        std::lock_guard<std::mutex> g(g_scratch_mu);
+        if (g_scratch_owner[r->device] != r || g_scratch_plan[r->device] != r->plan_version) {
+            bps::PackedItems packed;
+            for (size_t first = 0; first < n_items; first += bps::kPackedItemsPerLaunch) {
+                const uint32_t count = (uint32_t)std::min<size_t>(bps::kPackedItemsPerLaunch, n_items - first);
+                for (uint32_t k = 0; k < count; ++k) {
+                    const bps::WorkItem& it = r->plan_items[first + k];
+                    packed.word[k] = it.env | (it.scene << 16) | (it.tile << 28);
+                }
+                bps::launch_unpack_items(stream, packed, (uint32_t)first, count, d_items);
+                BPS_HIP(r, hipGetLastError());
+            }
+            g_scratch_owner[r->device] = r;
+            g_scratch_plan[r->device] = r->plan_version;
+        }
+    }
+    const bps::FrameParams fp = frame_params(r, 1);
+    const bool planned = fp_cull_enabled(r) && n_items > (size_t)2 * r->num_cu && !(r->cfg.flags & BPS_FLAG_NO_DISPATCH_ORDER);
+    if (planned) {
+        bps::launch_plan(stream, r->d_scenes, d_items, view_proj, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
+        BPS_HIP(r, hipGetLastError());
+    }
+    bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, planned ? d_ordered : d_items, view_proj,
+                       fp, nullptr, out_depth, out_tri_id, nullptr);
+    BPS_HIP(r, hipGetLastError());
+    BPS_HIP(r, hipEventRecord(slot.done, stream));
+    slot.pending = true;
+    slot.seq = seq;
+    r->last_splits = 1;
     r->last_groups = (uint64_t)n_items;
     return BPS_OK;
 }

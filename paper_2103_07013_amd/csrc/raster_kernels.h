@@ -105,6 +105,14 @@ constexpr uint32_t kMaxPlannedItems = 16384;
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
                  const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch, WorkItem* ordered);
 hipError_t prepare_raster(int threads, size_t lds);
+// Work items handed over as kernel arguments (no host-to-device copy, no staging memory): up to
+// kPackedItemsPerLaunch items per launch, each packed as env | scene << 16 | tile << 28 (one
+// work-group per environment and tile, i.e. split_of = 1 << 16).
+constexpr uint32_t kPackedItemsPerLaunch = 960;
+struct PackedItems {
+    uint32_t word[kPackedItemsPerLaunch];
+};
+void launch_unpack_items(hipStream_t stream, const PackedItems& packed, uint32_t first, uint32_t count, WorkItem* items);
 void launch_downsample(hipStream_t stream, const float* depth, const uint8_t* rgb, uint32_t B, int H, int W,
                        float* out_depth, uint8_t* out_rgb);
 // Colour pass.  Pixels whose winning triangle needs the clipper go through kShadeQueues queues (work-group g

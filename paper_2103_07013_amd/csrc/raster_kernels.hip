@@ -1114,6 +1114,23 @@ void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* ite
     hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), 0, stream, cost, n_items, dispatch, items, ordered);
 }
 
+__global__ __launch_bounds__(64) void k_unpack_items(PackedItems packed, uint32_t first, uint32_t count,
+                                                     WorkItem* __restrict__ items) {
+    const uint32_t k = blockIdx.x * 64u + threadIdx.x;
+    if (k >= count) return;
+    const uint32_t w = packed.word[k];
+    WorkItem it;
+    it.env = w & 0xFFFFu;
+    it.scene = (w >> 16) & 0xFFFu;
+    it.split_of = 1u << 16;
+    it.tile = w >> 28;
+    items[first + k] = it;
+}
+
+void launch_unpack_items(hipStream_t stream, const PackedItems& packed, uint32_t first, uint32_t count, WorkItem* items) {
+    hipLaunchKernelGGL(k_unpack_items, dim3((count + 63u) / 64u), dim3(64), 0, stream, packed, first, count, items);
+}
+
 __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0ull;
