@@ -7,6 +7,14 @@ multi-room scenes of ~500k triangles, 1024 environments (256 per scene, interlea
 float32 depth.  Scenes and view-projection matrices are resident in HBM before the timed region.
 Prints ONE JSON line.
 
+How the headline is timed: the K steps cycle through four seeded sets of camera poses (the
+workload's own and three more for the same scenes), the fourth with the environments' scene ids
+permuted, so that consecutive requests differ and the work items are re-staged now and then.
+Nothing but the requests is enqueued inside the timed region (no events); the region is bracketed
+by synchronisations and `value` is B K / wall time.  Two separate short passes follow: one with a
+HIP event per request (median and minimum time of a whole request), one with the library's events
+around the raster kernel alone (kernel time for the roofline).
+
 Two roofline objects are reported, both against the published HBM peak:
   roofline              the timed configuration (cluster culling on).  Algorithmic bytes are
                         recomputed for culling: bounds of every block / cluster that was tested plus
@@ -26,7 +34,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-PROFILE_EVERY = 4               # the events cost ~6 us per request: time a quarter of the launches
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4      # wave64 vector instructions per second: 256 CUs x 4 SIMDs, 4 cycles each
 
 
@@ -62,41 +69,83 @@ def measured_traffic(key):
         return None
 
 
-def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False, textured=False,
-              profile_every=1):
+def pose_cycle(torch, w, n_sets=4):
+    """n_sets requests for one workload: (scene ids, device matrices).  Set 0 is the workload's own
+    poses; the others are further seeded poses for the same scenes; the last one also permutes which
+    environment uses which scene (same multiset of scenes, other order)."""
+    import synth
+    out = []
+    for p in range(n_sets):
+        vp = w.view_proj if p == 0 else synth.more_poses(w, p)
+        ids = w.scene_ids
+        if p == n_sets - 1 and n_sets > 1:
+            perm = np.random.default_rng(7000 + w.number).permutation(w.B)
+            ids, vp = w.scene_ids[perm], np.ascontiguousarray(vp[perm])
+        out.append((ids, torch.from_numpy(np.ascontiguousarray(vp)).cuda()))
+    return out
+
+
+def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=False, textured=False, n_sets=4,
+              kernel_pass=24, request_pass=40):
     mode = bps.MODE_RGBD if w.rgbd else bps.MODE_DEPTH
     r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, mode=mode, splits=splits, threads=threads, flags=flags)
     if textured and w.rgbd:
         handles = [r.load_scene_textured(s.vertices, s.indices, s.uvs, s.texture) for s in w.scenes]
     else:
         handles = [r.load_scene(s.vertices, s.indices, s.colors if w.rgbd else None) for s in w.scenes]
-    ids = np.array([handles[k] for k in w.scene_ids], np.int32)
-    vp = torch.from_numpy(w.view_proj).cuda()
+    hmap = np.array(handles, np.int32)
+    cycle = [(hmap[ids], vp) for ids, vp in pose_cycle(torch, w, n_sets)]
     depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
     rgb = torch.empty((w.B, w.H, w.W, 3), dtype=torch.uint8, device="cuda") if w.rgbd else None
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
+
+    def submit(k):
+        ids, vp = cycle[k % len(cycle)]
         bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
+
+    for k in range(max(warmup, len(cycle))):
+        submit(k)
+    # ---- the headline: K requests, nothing else enqueued, bracketed by synchronisations
     torch.cuda.synchronize()
-    bps.bps_set_profiling(r.handle, profile_every)       # HIP events around every n-th raster launch of the timed region
     t0 = time.perf_counter()
-    for _ in range(steps):
-        bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
+    for k in range(steps):
+        submit(k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # ---- whole requests one by one: an event after every request (these cost a few microseconds each,
+    # which is why they are kept out of the headline)
+    n = request_pass
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record(stream)
+    for k in range(n):
+        submit(k)
+        ev[k + 1].record(stream)
+    torch.cuda.synchronize()
+    req_ms = np.array([ev[k].elapsed_time(ev[k + 1]) for k in range(n)])
+    # ---- the raster kernel alone (library events around its launch)
+    bps.bps_set_profiling(r.handle, 1)
+    for k in range(kernel_pass):
+        submit(k)
+    torch.cuda.synchronize()
     each = bps.bps_kernel_ms_each(r.handle)
-    launches, kernel_ms = len(each), float(each.sum())
     bps.bps_set_profiling(r.handle, False)
-    res = dict(dt=dt, kernel_ms_avg=kernel_ms / max(launches, 1), launches=launches,
+    launches = len(each)
+    res = dict(dt=dt, kernel_ms_avg=float(each.mean()) if launches else None, launches=launches,
                kernel_ms_median=float(np.median(each)) if launches else None,
                kernel_ms_min=float(each.min()) if launches else None,
+               request_ms_median=float(np.median(req_ms)), request_ms_min=float(req_ms.min()), requests_timed=n,
                clusters=[bps.bps_query(r.handle, h, 0) for h in handles],
                splits=bps.bps_query(r.handle, handles[0], 4), groups=bps.bps_query(r.handle, handles[0], 5),
                threads=bps.bps_query(r.handle, handles[0], 6), lds=bps.bps_query(r.handle, handles[0], 7))
     if diagnostics:
+        # work counts for the culling-aware byte accounting: averaged over the pose sets of the cycle
         bps.bps_set_diagnostics(r.handle, 1)
-        bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
-        res["diag"] = bps.bps_read_diagnostics(r.handle, 1 << 20).reshape(-1, 16).astype(np.float64)
+        diag = None
+        for k in range(len(cycle)):
+            submit(k)
+            d = bps.bps_read_diagnostics(r.handle, 1 << 22).reshape(-1, 16).astype(np.float64)
+            diag = d if diag is None else diag + d
+        res["diag"] = diag / len(cycle)
         bps.bps_set_diagnostics(r.handle, 0)
     r.close()
     return res
@@ -107,17 +156,16 @@ def inputs_ready_run(bps, torch, w, steps, warmup):
     the timed region, are declared complete at every call, so the renderer stages and plans each
     request on its own stream while the previous one is still being drawn."""
     r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W, flags=bps.FLAG_INPUTS_READY)
-    handles = [r.load_scene(s.vertices, s.indices) for s in w.scenes]
-    ids = np.array([handles[k] for k in w.scene_ids], np.int32)
-    vp = torch.from_numpy(w.view_proj).cuda()
+    hmap = np.array([r.load_scene(s.vertices, s.indices) for s in w.scenes], np.int32)
+    cycle = [(hmap[ids], vp) for ids, vp in pose_cycle(torch, w)]
     depth = torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+    for k in range(max(warmup, len(cycle))):
+        bps.bps_render(r.handle, *cycle[k % len(cycle)], depth, stream=stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+    for k in range(steps):
+        bps.bps_render(r.handle, *cycle[k % len(cycle)], depth, stream=stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     r.close()
@@ -129,19 +177,22 @@ def in_flight_run(bps, torch, w, steps, warmup, n_streams=2):
     so that consecutive requests overlap on the device and fill the compute units that the end of
     each launch leaves idle.  Reported beside the headline figure, which keeps one stream."""
     r = bps.Renderer(max_batch=w.B, height=w.H, width=w.W)
-    handles = [r.load_scene(s.vertices, s.indices) for s in w.scenes]
-    ids = np.array([handles[k] for k in w.scene_ids], np.int32)
-    vp = torch.from_numpy(w.view_proj).cuda()
+    hmap = np.array([r.load_scene(s.vertices, s.indices) for s in w.scenes], np.int32)
+    cycle = [(hmap[ids], vp) for ids, vp in pose_cycle(torch, w)]
     depth = [torch.empty((w.B, w.H, w.W), dtype=torch.float32, device="cuda") for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
-    for k in range(max(warmup, n_streams)):
-        bps.bps_render(r.handle, ids, vp, depth[k % n_streams], stream=streams[k % n_streams])
+    for k in range(max(warmup, len(cycle))):
+        bps.bps_render(r.handle, *cycle[k % len(cycle)], depth[k % n_streams], stream=streams[k % n_streams])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        bps.bps_render(r.handle, ids, vp, depth[k % n_streams], stream=streams[k % n_streams])
+        bps.bps_render(r.handle, *cycle[k % len(cycle)], depth[k % n_streams], stream=streams[k % n_streams])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # the same request on each stream must give the same frames
+    for d, st in zip(depth, streams):
+        bps.bps_render(r.handle, *cycle[0], d, stream=st)
+    torch.cuda.synchronize()
     same = all(bool((d == depth[0]).all()) for d in depth[1:])
     r.close()
     return {"requests_in_flight": n_streams, "value": w.B * steps / dt, "unit": "frames/s", "steps": steps,
@@ -178,7 +229,7 @@ def rotation_run(bps, torch, w, steps, warmup):
             slot_handles[k] = new
             with lock:
                 state["ids"] = np.array([slot_handles[j] for j in w.scene_ids], np.int32)
-            bps.bps_unload_scene(r.handle, old)         # requests that still use it are queued: allowed
+                bps.bps_unload_scene(r.handle, old)     # requests that still use it are queued: allowed
             state["loaded"] += 1
             n += 1
 
@@ -189,9 +240,8 @@ def rotation_run(bps, torch, w, steps, warmup):
     th.start()
     t0 = time.perf_counter()
     for _ in range(steps):
-        with lock:
-            ids = state["ids"]
-        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+        with lock:      # the loader retires the old handle only after taking this lock: never between snapshot and request
+            bps.bps_render(r.handle, state["ids"], vp, depth, stream=stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     state["stop"] = True
@@ -216,7 +266,7 @@ def sweep(bps, torch, steps, warmup):
             reps = (B + base.B - 1) // base.B
             w = synth.Workload(3, base.scenes, np.tile(base.scene_ids, reps)[:B], np.tile(base.view_proj, (reps, 1, 1))[:B],
                                res, res, False)
-            run = timed_run(bps, torch, w, 0, steps, warmup, 0, 0)
+            run = timed_run(bps, torch, w, 0, steps, warmup, 0, 0, n_sets=1, request_pass=4)
             print(json.dumps({"sweep": True, "B": B, "H": res, "W": res, "frames_per_s": B * steps / run["dt"],
                               "ms_per_request": run["dt"] * 1e3 / steps, "kernel_ms": run["kernel_ms_avg"],
                               "work_groups": run["groups"], "splits": run["splits"]}), flush=True)
@@ -241,6 +291,9 @@ def main():
     ap.add_argument("--textured", action="store_true",
                     help="RGB-D workloads: colour from each scene's texture (uv + mip pyramid) instead of vertex colours")
     ap.add_argument("--rotate", action="store_true", help="also time rendering while scenes are being replaced")
+    ap.add_argument("--jitter", type=float, default=0.0, metavar="CELLS",
+                    help="time the workload on its irregular variant: furniture turned off-axis and every vertex displaced "
+                         "by up to this many grid cells (multi-room workloads; 0 = the regular scenes)")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed run: no diagnostics request, no full-stream run (for profiler runs)")
     ap.add_argument("--cpu-envs", type=int, default=512, help="environments in the oracle timing sample (0 = skip)")
@@ -274,14 +327,13 @@ def main():
     if args.sweep:
         sweep(bps, torch, min(args.steps, 30), 5)
         return
-    w = synth.build_config(args.config, B=args.batch)
+    w = synth.build_config(args.config, B=args.batch, jitter=args.jitter)
     flags = ((bps.FLAG_NO_CLUSTER_CULL if args.no_cull else 0) | (bps.FLAG_NO_OCCLUSION_CULL if args.no_occlusion else 0) |
              (bps.FLAG_NO_DISPATCH_ORDER if args.no_dispatch_order else 0) |
              (bps.FLAG_INPUTS_READY if args.inputs_ready else 0))
     culling = not args.no_cull
     main_run = timed_run(bps, torch, w, flags, args.steps, args.warmup, args.splits, args.threads,
-                         diagnostics=culling and not args.no_extras, textured=args.textured,
-                         profile_every=PROFILE_EVERY if args.steps >= 80 else 1)
+                         diagnostics=culling and not args.no_extras, textured=args.textured)
     dt = main_run["dt"]
     kernel_ms_avg = main_run["kernel_ms_avg"]
     variant = "full_stream" if args.no_cull else ("frustum_cull" if args.no_occlusion else "cull")
@@ -311,9 +363,13 @@ def main():
         if nbytes is None:
             return None
         achieved = nbytes / (ms * 1e-3) / 1e9
+        traffic = measured_traffic(traffic_key)
         out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-               "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(traffic_key), "kernel": "k_raster",
-               "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes, "accounting": note}
+               "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+               # what the counters say really crossed between L2 and the memory side, as a rate and against the peak
+               "traffic_GBs": None if traffic is None else traffic / (ms * 1e-3) / 1e9,
+               "traffic_frac": None if traffic is None else traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               "kernel": "k_raster", "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes, "accounting": note}
         valu = measured_traffic(traffic_key + "_valu_insts")
         if valu:
             # what the counters say binds the kernel: vector-ALU issue (1024 SIMDs, 4 cycles per wave64 instruction)
@@ -339,7 +395,7 @@ def main():
         return 2.0 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
     out = {
-        "metric": "rendered frames/sec (64x64 depth, 1024 envs) on 1 MI355X",
+        "metric": f"rendered frames/sec ({w.H}x{w.W} {'RGB-D' if w.rgbd else 'depth'}, {w.B} envs) on 1 MI355X",
         "value": w.B * args.steps / dt,
         "unit": "frames/s",
         "n_gpus": 1,
@@ -355,7 +411,7 @@ def main():
             "workload": f"config{w.number}: {len(w.scenes)} procedural {'multi-room' if w.number > 1 else 'room'} scenes x "
                         f"~{w.scenes[0].T} triangles, {w.B} environments (scene = b mod {len(w.scenes)}), "
                         f"{w.H}x{w.W} {('textured RGB-D' if args.textured else 'RGB-D') if w.rgbd else 'float32 depth'}",
-            "variant": variant,
+            "variant": variant + (f", irregular geometry (jitter {args.jitter})" if args.jitter else ""),
             "B": w.B, "H": w.H, "W": w.W, "scenes": len(w.scenes),
             "triangles_per_scene": [s.T for s in w.scenes],
             "env_triangles_per_step": w.env_triangles,
@@ -363,6 +419,11 @@ def main():
             "lds_bytes": main_run["lds"],
         },
         "env_triangles_per_s": w.env_triangles * args.steps / dt,
+        "request_ms_median": main_run["request_ms_median"], "request_ms_min": main_run["request_ms_min"],
+        "requests_timed_one_by_one": main_run["requests_timed"],
+        "timing": "value = B x steps / wall time of the steps (bracketed by synchronisations; requests cycle through 4 "
+                  "pose sets, one of them with permuted scene ids); request_ms_* from a separate pass with a HIP event "
+                  "after every request; roofline.kernel_ms_* from a third pass with events around the raster kernel",
         "roofline": roofline(abytes, kernel_ms_avg, accounting, f"config{w.number}_{variant}"),
     }
     if out["roofline"] is not None:
@@ -392,6 +453,20 @@ def main():
         out["two_requests_in_flight"] = in_flight_run(bps, torch, w, args.steps, args.warmup)
         if not args.inputs_ready:
             out["inputs_declared_ready"] = inputs_ready_run(bps, torch, w, args.steps, args.warmup)
+    if culling and not args.no_extras and not w.rgbd and w.number > 1 and not args.jitter:
+        # the same workload on irregular geometry (furniture turned off-axis, every vertex displaced by up to 0.3 grid
+        # cells): shows what the cluster packing and the culling owe to axis-aligned, regular grids
+        wj = synth.build_config(args.config, B=args.batch, jitter=0.3)
+        steps2 = max(10, args.steps // 2)
+        rj = timed_run(bps, torch, wj, flags, steps2, 5, args.splits, args.threads, diagnostics=True)
+        dj = rj["diag"]
+        out["irregular_geometry"] = {
+            "what": "same configuration with the scenes' furniture turned about its vertical axis by random angles and "
+                    "every vertex displaced by up to 0.3 grid cells per axis (bench.py --jitter 0.3 times it alone)",
+            "value": wj.B * steps2 / rj["dt"], "unit": "frames/s", "ms_per_step": rj["dt"] * 1e3 / steps2,
+            "kernel_ms_median": rj["kernel_ms_median"], "clusters_drawn": int(dj[:, 2].sum()),
+            "clusters_in_batch": int(sum(rj["clusters"][s] for s in wj.scene_ids)),
+            "triangles_per_scene": [s.T for s in wj.scenes]}
     if args.rotate and not w.rgbd:
         out["rotation"] = rotation_run(bps, torch, w, max(2000, args.steps), args.warmup)
     if args.cpu_envs > 0:

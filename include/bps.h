@@ -191,6 +191,12 @@ bps_status bps_kernel_ms_each(bps_renderer *r, float *out, uint32_t capacity, ui
  *   [9..15] with enable = 2 only (this slows the kernel): time summed over the group's wavefronts
  *           in the bounds testing, barrier, depth sort, prologue (set-up and block ordering),
  *           cluster processing, barrier and final flush phases.
+ *           with enable = 3: how often each path ran, summed over the wavefronts: drains of the
+ *           small-triangle queue, their pixel steps, the steps in which some pixel was covered, calls that
+ *           handed triangles on, passes over medium triangles, 8x8 steps of large ones, appends to the queue.
+ *           with enable = 4: clipper runs, their plane passes, fan steps, occlusion-test passes when
+ *           clusters are taken off the list, passes over 64 triangles, clusters taken off the list,
+ *           passes of the bounds tests.
  *   with enable = 1 instead: [11] environment index, [12] run times of all the group's wavefronts
  *           summed, [13] start and [14] end of the group on the device-wide 100 MHz clock (low 32
  *           bits), [15] hardware id of the compute unit that ran it (die in the top byte).

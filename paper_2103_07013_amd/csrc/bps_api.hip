@@ -114,7 +114,8 @@ struct bps_renderer {
     uint32_t shade_parity = 0;            // which of the two counters the next RGB-D request uses
     unsigned long long* d_stats = nullptr;   // diagnostics block: 8 counters + one duration per work-group
     size_t stats_cap = 0;
-    bool want_stats = false, want_phase_timers = false;
+    bool want_stats = false;
+    int stats_mode = 0;                   // 0 counters + timeline, 1 phase timers, 2 / 3 path tallies
     std::vector<hipEvent_t> ev;           // profiling: pairs (start, stop), one pair per request
     size_t ev_used = 0;
     bool profiling = false;
@@ -261,7 +262,7 @@ bps::FrameParams frame_params(const bps_renderer* r, int S) {
     fp.list_cap = r->list_cap;
     fp.round_target = r->round_target;
     fp.first_round = r->first_round;
-    fp.phase_timers = (r->want_stats && r->want_phase_timers) ? 1 : 0;
+    fp.phase_timers = r->want_stats ? r->stats_mode : 0;
     return fp;
 }
 
@@ -322,7 +323,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         r->tile_h = tile_of(r->rh);
         if (const char* e = std::getenv("BPS_TILE")) {   // tuning knob: force a tile size
             int v = std::atoi(e);
-            if (v >= 8 && v <= 128) { r->tile_w = std::min(v, r->rw); r->tile_h = std::min(v, r->rh); }
+            if (v >= 8 && v <= 64) { r->tile_w = std::min(v, r->rw); r->tile_h = std::min(v, r->rh); }   // a window is at most 64x64 pixels
         }
         r->tiles = ((r->rw + r->tile_w - 1) / r->tile_w) * ((r->rh + r->tile_h - 1) / r->tile_h);
         // preferred work-group size whose LDS footprint leaves room for a useful survivor list
@@ -1084,7 +1085,7 @@ bps_status bps_kernel_ms_each(bps_renderer* r, float* out, uint32_t capacity, ui
 bps_status bps_set_diagnostics(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
     r->want_stats = enable != 0;
-    r->want_phase_timers = enable > 1;
+    r->stats_mode = enable > 1 ? (enable <= 4 ? enable - 1 : 1) : 0;
     return BPS_OK;
 }
 

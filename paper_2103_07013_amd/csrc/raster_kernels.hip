@@ -20,8 +20,12 @@ struct WaveLds {
     uint32_t* stage_oc; // [64] their outcodes
     uint32_t* smallq;   // [8][64] struct-of-arrays: xy0 xy1 xy2 iw0 iw1 iw2 id box
     uint32_t* clipq;    // [192] cluster << 7 | slot
-    uint32_t* tally;    // diagnostics: [0] small triangles queued, [1] large triangles rasterised (wave-private registers)
+    uint32_t* tally;    // diagnostics (wave-private registers, dead code in the production instances): see kT*
 };
+// diagnostics tallies
+enum { kTSmall = 0, kTLarge = 1, kTDrains = 2, kTDrainIters = 3, kTDrainDepth = 4, kTEmits = 5, kTMedPasses = 6, kTLargeSteps = 7,
+       kTPushes = 8, kTClipDrains = 9, kTClipPasses = 10, kTFanIters = 11, kTPopPasses = 12, kTSlots = 13, kTClusters = 14,
+       kTPhaseAPasses = 15, kTCount = 16 };
 
 // One lane per queued small triangle: at most kSmallMax pixel centres each.
 __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u64* vis, const Window& win,
@@ -52,9 +56,12 @@ __device__ __forceinline__ void drain_small(const WaveLds& L, int n, int lane, u
     int at = __mul24(j_lo - win.y0, win.w) + (i_lo - win.x0), col = 0;
     const int at_wrap = win.w - nx + 1;
     const float a2f = (float)s.A2;
+    ++L.tally[kTDrains];
     for (int k = 0; k < kSmallMax; ++k) {
         const bool act = k < cnt;
         if (ballot64(act) == 0) break;
+        ++L.tally[kTDrainIters];
+        if (ballot64(act && (((E0 + s.b0) | (E1 + s.b1) | (E2 + s.b2)) >= 0)) != 0ull) ++L.tally[kTDrainDepth];
         if (act && (((E0 + s.b0) | (E1 + s.b1) | (E2 + s.b2)) >= 0)) {
             const float num = fmaf((float)E2, s.iw2, fmaf((float)E1, s.iw1, (float)E0 * s.iw0));
             const float depth = a2f / num;
@@ -78,7 +85,8 @@ __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool wa
     // which cost one compare each, instead of a ballot of the combined condition)
     if (mask == 0) return;
     int n = __popcll(mask);
-    L.tally[0] += (uint32_t)n;
+    L.tally[kTSmall] += (uint32_t)n;
+    ++L.tally[kTPushes];
     int rank = (int)rank_below(mask);
     int room = 64 - count;
     int pos = count + rank;            // position if the queue were unbounded
@@ -110,7 +118,7 @@ __device__ __forceinline__ void push_small(const WaveLds& L, int& count, bool wa
 // Whole wavefront on one large triangle: 8x8 pixel blocks over its bounding box.
 __device__ __forceinline__ void raster_large(uint32_t xy0, uint32_t xy1, uint32_t xy2, float iw0, float iw1, float iw2,
                                              uint32_t id, int i_lo, int i_hi, int j_lo, int j_hi, int lane, u64* vis,
-                                             const Window& win) {
+                                             const Window& win, uint32_t* tally) {
     Setup s = make_setup(xy0, xy1, xy2, iw0, iw1, iw2);
     int li = lane & 7, lj = lane >> 3;
     for (int by = j_lo >> 3; by <= (j_hi >> 3); ++by) {
@@ -119,6 +127,7 @@ __device__ __forceinline__ void raster_large(uint32_t xy0, uint32_t xy1, uint32_
         for (int bx = i_lo >> 3; bx <= (i_hi >> 3); ++bx) {
             int i = (bx << 3) + li;
             bool act = jok && i >= i_lo && i <= i_hi;
+            ++tally[kTLargeSteps];
             shade_pixel(s, i, j, act, id, vis, win);
         }
     }
@@ -157,6 +166,7 @@ __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool va
                                      const Window& win, u64 vmask) {
     // vmask = the lanes with valid set
     if (vmask == 0) return;
+    ++L.tally[kTEmits];
     int nx = (int)ext.x + 1, ny = (int)ext.y + 1;
     int i_lo = (int)lo.x + 64, j_lo = (int)lo.y + 64;
     const bool few = nx * ny <= kSmallMax, narrow = nx <= 8, low = ny <= 8;
@@ -166,10 +176,11 @@ __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool va
     push_small(L, small_count, small, xy0, xy1, xy2, iw0, iw1, iw2, ref, box, lane, vis, win, ctri_id, small_mask);
     u64 med = vmask & ~small_mask & ballot64(narrow) & ballot64(low);
     u64 big = vmask & ~small_mask & ~med;
-    L.tally[1] += (uint32_t)__popcll(med | big);
+    L.tally[kTLarge] += (uint32_t)__popcll(med | big);
     const uint32_t id = (valid && !small) ? ctri_id[ref] : 0u;
     // medium triangles (box within 8x8 pixels): four per pass, sixteen lanes each, 4x4 pixels per step
     while (med) {
+        ++L.tally[kTMedPasses];
         int src[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -204,7 +215,7 @@ __device__ __forceinline__ void emit(const WaveLds& L, int& small_count, bool va
         int bi = bcast_i(i_lo, src), bj = bcast_i(j_lo, src);
         raster_large((uint32_t)bcast_i((int)xy0, src), (uint32_t)bcast_i((int)xy1, src), (uint32_t)bcast_i((int)xy2, src),
                      bcast_f(iw0, src), bcast_f(iw1, src), bcast_f(iw2, src), (uint32_t)bcast_i((int)id, src), bi,
-                     bi + bcast_i(nx, src) - 1, bj, bj + bcast_i(ny, src) - 1, lane, vis, win);
+                     bi + bcast_i(nx, src) - 1, bj, bj + bcast_i(ny, src) - 1, lane, vis, win, L.tally);
     }
 }
 
@@ -352,7 +363,9 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
         }
     }
     bool first_pass = true;
+    ++L.tally[kTClipDrains];
     while (ballot64(todo != 0u) != 0ull) {
+        ++L.tally[kTClipPasses];
         const bool active = todo != 0u;
         const int p = active ? __builtin_ctz(todo) : 0;
         todo &= todo - 1u;
@@ -431,6 +444,7 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
         bool v = i + 1 < cnt;
         const u64 vm = ballot64(v);
         if (vm == 0) break;
+        ++L.tally[kTFanIters];
         const uint32_t d = d_ahead;
         const float wd = wd_ahead;
         d_ahead = pxy[min(i + 2, kMaxPoly - 1)];
@@ -463,7 +477,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     // The DIAG = false instance carries no counters or timers at all: everything below that feeds
     // only the diagnostics record is dead code there and costs neither registers nor instructions.
     unsigned long long* const stats = DIAG ? stats_block : nullptr;
-    const bool phase_timers = DIAG && fp.phase_timers != 0;
+    const bool phase_timers = DIAG && fp.phase_timers == 1;
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -482,7 +496,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 
     u64* vis = reinterpret_cast<u64*>(smem);
     unsigned char* wbase = smem + (size_t)HW * 8 + (size_t)wave * kWaveLdsBytes;
-    uint32_t tally[2] = {0u, 0u};
+    uint32_t tally[kTCount] = {};
     WaveLds L;
     L.tally = tally;
     L.stage = reinterpret_cast<float2*>(wbase);
@@ -637,6 +651,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 if (lane == 0) atomicSub(reserved, 64u);
                 continue;
             }
+            ++tally[kTPhaseAPasses];
             const uint32_t cl = (jb * S + item_split) * 64u + (uint32_t)lane;
             bool visible = cl < sc.n_clusters;
             uint32_t foot = 0u, wb18 = 0u;
@@ -762,6 +777,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                     const int rows_per_pass = 64 >> cols_log2;
                     bool shows = false;
                     for (int row0 = 0; row0 <= bh && !shows; row0 += rows_per_pass) {
+                        ++tally[kTPopPasses];
                         const bool in = qx <= bw && row0 + qy <= bh;
                         const uint32_t d = in ? vis_hi[2 * (__mul24(fy + row0 + qy, win.w) + fx + qx)] : 0u;
                         // lanes outside the footprint read d = 0, below every bound (the bound is a positive float)
@@ -790,6 +806,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
             bool o4 = !(cp.z >= 0.0f), o5 = !(cp.w - cp.z >= 0.0f);
             bool culled = ballot64(o0) == ~0ull || ballot64(o1) == ~0ull || ballot64(o2) == ~0ull ||
                           ballot64(o3) == ~0ull || ballot64(o4) == ~0ull || ballot64(o5) == ~0ull;
+            ++tally[kTClusters];
             if (culled) continue;
             ++st_drawn;
             uint32_t oc = (o0 ? 1u : 0u) | (o1 ? 2u : 0u) | (o2 ? 4u : 0u) | (o3 ? 8u : 0u) | (o4 ? 16u : 0u) |
@@ -817,6 +834,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
 #pragma unroll 1
             for (int slot = 0; slot < 2; ++slot) {
                 if (slot == 1 && ntri <= 64) break;
+                ++tally[kTSlots];
                 uint32_t t = (slot == 0 ? t0 : t1) & full_tri_mask;
                 const uint32_t i0 = t & 0xFFu, i1 = (t >> 8) & 0xFFu, i2 = t >> 16;
                 float2 a = L.stage[i0], b = L.stage[i1], d = L.stage[i2];
@@ -924,9 +942,12 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         uint32_t* rec = reinterpret_cast<uint32_t*>(list) + wave * 16;
         const uint32_t dt = (uint32_t)(wall_clock64() - t_start);
         rec[0] = st_tested; rec[1] = st_boxed; rec[2] = st_drawn; rec[3] = st_straddle; rec[4] = st_hidden; rec[5] = dt;
-        rec[6] = tally[0]; rec[7] = tally[1]; rec[8] = st_hiz;
+        rec[6] = tally[kTSmall]; rec[7] = tally[kTLarge]; rec[8] = st_hiz;
         for (int k = 1; k < 8; ++k) rec[8 + k] = ticks[k];
-        if (!phase_timers) {
+        // path tallies instead of the phase timers: first or second half of them
+        if (fp.phase_timers == 2) for (int k = 0; k < 7; ++k) rec[9 + k] = tally[2 + k];
+        if (fp.phase_timers == 3) for (int k = 0; k < 7; ++k) rec[9 + k] = tally[9 + k];
+        if (fp.phase_timers == 0) {
             // without phase timers the last words tell where and when the group ran: the sum of the
             // wavefronts' durations (against word 5: how unevenly they finish), the environment, start
             // and end on the device-wide 100 MHz clock, and the hardware id (compute unit, shader

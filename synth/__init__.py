@@ -11,10 +11,10 @@ yaws (Appendix A.3, agent actions).
 """
 from .scenes import Scene, make_room_scene, make_multiroom_scene
 from .cameras import make_cameras, perspective, look_yaw, view_proj_from_pose
-from .configs import CONFIGS, build_config, Workload
+from .configs import CONFIGS, build_config, more_poses, Workload
 
 __all__ = [
     "Scene", "make_room_scene", "make_multiroom_scene", "make_cameras",
     "perspective", "look_yaw", "view_proj_from_pose", "CONFIGS",
-    "build_config", "Workload",
+    "build_config", "more_poses", "Workload",
 ]

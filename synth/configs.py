@@ -41,9 +41,12 @@ class Workload:
                 f"B={self.B}, {self.H}x{self.W} {'rgbd' if self.rgbd else 'depth'}")
 
 
-def build_config(number, B=None, scale=1.0):
+def build_config(number, B=None, scale=1.0, jitter=0.0, pose_set=0):
     """Build workload `number`.  B overrides the environment count; scale < 1 shrinks the
-    per-scene triangle target (for quick CPU tests of the same structure)."""
+    per-scene triangle target (for quick CPU tests of the same structure); jitter > 0 gives the
+    irregular variant of the multi-room scenes (furniture turned off-axis, vertices displaced by
+    up to jitter x the grid cell); pose_set > 0 draws another seeded set of camera poses for the
+    same scenes (pose_set 0 is the workload's own)."""
     c = CONFIGS[number]
     K = c["K"]
     B = c["B"] if B is None else B
@@ -53,13 +56,25 @@ def build_config(number, B=None, scale=1.0):
         if c["kind"] == "room":
             scenes.append(make_room_scene(T, seed=1000 + k))
         else:
-            scenes.append(make_multiroom_scene(T, seed=1000 + k))
+            scenes.append(make_multiroom_scene(T, seed=1000 + k, jitter=jitter))
     scene_ids = (np.arange(B) % K).astype(np.int32)
     vp = np.empty((B, 4, 4), np.float32)
     aspect = c["W"] / c["H"]
     for k in range(K):
         sel = np.nonzero(scene_ids == k)[0]
         if sel.size:
-            m, _ = make_cameras(scenes[k], sel.size, seed=(2000 + number) * 100 + k, aspect=aspect)
+            m, _ = make_cameras(scenes[k], sel.size, seed=(2000 + number) * 100 + k + 100_000 * pose_set, aspect=aspect)
             vp[sel] = m
     return Workload(number, scenes, scene_ids, vp, c["H"], c["W"], c["rgbd"])
+
+
+def more_poses(w, pose_set):
+    """Another seeded set of camera poses [B,4,4] for the scenes and scene ids of workload w."""
+    vp = np.empty_like(w.view_proj)
+    K = len(w.scenes)
+    for k in range(K):
+        sel = np.nonzero(w.scene_ids == k)[0]
+        if sel.size:
+            m, _ = make_cameras(w.scenes[k], sel.size, seed=(2000 + w.number) * 100 + k + 100_000 * pose_set, aspect=w.W / w.H)
+            vp[sel] = m
+    return vp

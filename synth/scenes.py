@@ -240,8 +240,31 @@ def make_room_scene(target_T=10_000, seed=1000, n_boxes=20):
                  boxes=fp, cell=cell, seed=seed)
 
 
-def make_multiroom_scene(target_T=200_000, seed=1000, n_objects=150, rooms=(3, 2)):
-    """rooms[0] x rooms[1] grid of rooms joined by doorways, with boxes and cylinders."""
+def _make_irregular(P, obj, first_furniture, objs, cell, jitter, seed):
+    """Irregular variant of a scene: every piece of furniture is turned about its vertical axis by a
+    seeded angle (its faces stop being axis-aligned) and every vertex is displaced by up to
+    `jitter` x cell in each axis (grids stop being regular, faces stop being planar).
+    Returns the new positions and the axis-aligned footprints of the turned boxes."""
+    rng = np.random.default_rng(seed + 7919)
+    P = P.copy()
+    footprints = []
+    for k, o in enumerate(objs):
+        m = obj == first_furniture + k
+        c = 0.5 * (P[m][:, [0, 2]].min(0) + P[m][:, [0, 2]].max(0))
+        a = rng.uniform(0.0, 2.0 * math.pi)
+        ca, sa = math.cos(a), math.sin(a)
+        dx, dz = P[m, 0] - c[0], P[m, 2] - c[1]
+        P[m, 0] = c[0] + ca * dx - sa * dz
+        P[m, 2] = c[1] + sa * dx + ca * dz
+        if o[0] == "box":
+            footprints.append([P[m, 0].min(), P[m, 2].min(), P[m, 0].max(), P[m, 2].max()])
+    P += rng.uniform(-jitter, jitter, size=P.shape) * cell
+    return P, np.array(footprints).reshape(-1, 4)
+
+
+def make_multiroom_scene(target_T=200_000, seed=1000, n_objects=150, rooms=(3, 2), jitter=0.0):
+    """rooms[0] x rooms[1] grid of rooms joined by doorways, with boxes and cylinders.
+    jitter > 0 gives the irregular variant (see _make_irregular)."""
     rng = np.random.default_rng(seed)
     RX, RZ = rooms
     SX, SZ = RX * ROOM_X, RZ * ROOM_Z
@@ -297,6 +320,10 @@ def make_multiroom_scene(target_T=200_000, seed=1000, n_objects=150, rooms=(3, 2
     colors = _colorize(rng, obj, mb.cur_obj)
     fp = np.array([[o[1], o[2], o[1] + o[3], o[2] + o[4]] for o in objs if o[0] == "box"]).reshape(-1, 4)
     cy = np.array([[o[1], o[2], o[3]] for o in objs if o[0] == "cyl"]).reshape(-1, 3)
+    if jitter > 0.0:
+        # objects are numbered in build order: floor, ceiling, four outer walls, the interior walls, then the furniture
+        first_furniture = 6 + len(doors_x) + len(doors_z) + 1
+        P, fp = _make_irregular(P, obj, first_furniture, objs, cell, jitter, seed)
     return Scene(P.astype(np.float32), Tt.astype(np.uint32), colors, uv.astype(np.float32), _texture(rng), (SX, SZ),
                  boxes=fp, cylinders=cy,
                  wall_x=tuple(i * ROOM_X for i in range(1, RX)),

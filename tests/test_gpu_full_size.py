@@ -68,7 +68,7 @@ def test_config5_128x128_large_batch():
 def test_ragged_batches_through_the_launch_planner(B):
     """Batch sizes that are not multiples of the planner's 64-item windows or of the die count, with
     scene ids in random order: the cost-ordered launch must still render every environment exactly
-    once, i.e. agree everywhere with a launch in plain batch order, and with the oracle on a sample."""
+    once, i.e. agree with a launch in plain batch order and, frame by frame, with the oracle."""
     import torch
     import oracle
     import paper_2103_07013_amd as bps
@@ -87,7 +87,6 @@ def test_ragged_batches_through_the_launch_planner(B):
             frames[name] = (depth.cpu().numpy(), tid.cpu().numpy().view(np.uint32))
     assert np.array_equal(frames["planned"][1], frames["batch order"][1])
     assert np.array_equal(frames["planned"][0], frames["batch order"][0])
-    sel = np.arange(0, B, 97)
-    ref = oracle.render_batch(w.scenes, scene_ids[sel], view_proj[sel], w.H, w.W)
-    assert np.array_equal(frames["planned"][1][sel], ref["tri_id"])
-    assert np.all(np.abs(frames["planned"][0][sel] - ref["depth"]) <= 1e-5 * np.abs(ref["depth"]))
+    ref = oracle.render_batch(w.scenes, scene_ids, view_proj, w.H, w.W)      # every environment
+    assert np.array_equal(frames["planned"][1], ref["tri_id"])
+    assert np.all(np.abs(frames["planned"][0] - ref["depth"]) <= 1e-5 * np.abs(ref["depth"]))
