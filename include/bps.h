@@ -32,7 +32,8 @@ extern "C" {
 #endif
 
 typedef struct bps_renderer bps_renderer; /* opaque; bound to one device and one frame format */
-typedef int32_t bps_scene;                /* handle >= 0 */
+typedef int32_t bps_scene;                /* handle >= 0; names one load: after bps_unload_scene it stays invalid even
+                                             when the library reuses its table slot for a later scene */
 typedef int32_t bps_status;
 
 enum {
@@ -73,9 +74,11 @@ typedef struct {
                                 2 height and 2 width must be <= 128 and out_tri_id must be NULL */
 } bps_config;
 
-/* Create a renderer on cfg->device.  *out receives the handle.  Allocates the device scene
- * table, the request staging ring and (lazily) the global visibility buffer used when an
- * environment is split over several work-groups. */
+/* Create a renderer on cfg->device (Sec. 3.2: the renderer is set up once and then serves one batched
+ * request per simulation step; its frame size is the policy's input resolution, Sec. 4.1).  *out
+ * receives the handle.  Allocates the device scene table, the events of the request staging ring
+ * and (lazily, in the first requests that need them) the staging buffers, the global visibility
+ * buffer used when an environment is split over several work-groups, and the colour pass's buffers. */
 bps_status bps_create(const bps_config *cfg, bps_renderer **out);
 
 /* Waits for the device, frees every scene and buffer.  NULL is ignored. */
@@ -127,9 +130,11 @@ bps_status bps_load_scene_textured(bps_renderer *r, const float *vertices, uint3
 bps_status bps_pack_clusters(const float *vertices, uint32_t V, const uint32_t *indices, uint32_t T, uint32_t *count,
                              float *verts_out, uint32_t *tris_out, uint32_t *ids_out);
 
-/* Retires a scene.  Safe while requests that reference it are still queued: its device block and
- * table slot are only reused after those requests have finished (no host wait).  The handle is
- * invalid for new requests from this call on. */
+/* Retires a scene (Sec. 3.2 "Scene asset sharing": the K resident assets are rotated, a scene that
+ * no environment uses any more makes room for the next one).  Safe while requests that reference
+ * it are still queued, and while its own asynchronous upload is still in flight: its device block and
+ * table slot are only reused after those have finished.  Never waits for the device.  The handle is
+ * invalid for new requests from this call on (BPS_ERR_BAD_HANDLE), also after its slot has been reused. */
 bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
 
 /* One batched render request (Sec. 3: the whole batch of N environment states is rendered at
@@ -141,7 +146,9 @@ bps_status bps_unload_scene(bps_renderer *r, bps_scene scene);
  *   out_tri_id  DEVICE uint32 [B][H][W] or NULL; winning triangle id, 0xFFFFFFFF = none
  *   stream      hipStream_t (NULL = default stream)
  * Only enqueues work on `stream` and returns; host arrays are consumed before return, output
- * buffers must stay alive until the stream reaches the end of the request.
+ * buffers must stay alive until the stream reaches the end of the request.  The one host wait: at
+ * most four requests of a renderer are in flight; a fifth call waits for the oldest to finish
+ * (its staging slot is reused).
  * Requests on one stream run in order.  Requests on different streams may overlap on the device
  * (two requests in flight fill the compute units that the end of a launch leaves idle); the library
  * itself orders those that use its internal buffers (RGB-D requests, split frames,

@@ -48,6 +48,10 @@ def _load():
         lib.oracle_cover_fixed.argtypes = [i32p, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, u32p]
         lib.oracle_clip.restype = ctypes.c_int
         lib.oracle_clip.argtypes = [f32p, f32p, f32p]
+        lib.oracle_clip_stats.restype = None
+        lib.oracle_clip_stats.argtypes = [i32p, i32p, ctypes.c_int]
+        lib.oracle_downsample2.restype = None
+        lib.oracle_downsample2.argtypes = [f32p, u8p, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, f32p, u8p]
         _lib = lib
     return _lib
 
@@ -85,7 +89,31 @@ def render_scene(vertices, indices, view_proj, H, W, colors=None, background=0.0
                                       _p(m, ctypes.c_float), B, H, W, float(background),
                                       _p(depth, ctypes.c_float), _p(tid, ctypes.c_uint32), _p(rgb, ctypes.c_uint8),
                                       _p(cover, ctypes.c_uint32), int(nthreads))
+    if used < 0:
+        raise RuntimeError("oracle: a clipped polygon needed more corners than the clipper holds")
     return dict(depth=depth, tri_id=tid, rgb=rgb, cover=cover, threads=used)
+
+
+def clip_stats(reset=False):
+    """(polygons that outgrew the clipper, largest corner count reached) since the last reset."""
+    lib = _load()
+    a, b = ctypes.c_int32(0), ctypes.c_int32(0)
+    lib.oracle_clip_stats(ctypes.byref(a), ctypes.byref(b), 1 if reset else 0)
+    return int(a.value), int(b.value)
+
+
+def downsample2(depth, rgb=None):
+    """2x2 box filter of supersampled frames: depth f32 [B,2H,2W] (and rgb u8 [B,2H,2W,3]) ->
+    (depth [B,H,W], rgb [B,H,W,3] | None)."""
+    lib = _load()
+    d = np.ascontiguousarray(depth, np.float32)
+    B, H2, W2 = d.shape
+    H, W = H2 // 2, W2 // 2
+    c = None if rgb is None else np.ascontiguousarray(rgb, np.uint8)
+    od = np.empty((B, H, W), np.float32)
+    oc = None if c is None else np.empty((B, H, W, 3), np.uint8)
+    lib.oracle_downsample2(_p(d, ctypes.c_float), _p(c, ctypes.c_uint8), B, H, W, _p(od, ctypes.c_float), _p(oc, ctypes.c_uint8))
+    return od, oc
 
 
 def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0, nthreads=0, want_cover=False,

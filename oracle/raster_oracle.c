@@ -100,6 +100,20 @@ static void intersect(const overt *a, const overt *b, int k, overt *o)
     for (int i = 0; i < 3; ++i) o->col[i] = fmaf(t, b->col[i] - a->col[i], a->col[i]);
 }
 
+/* The clipper's polygons hold MAXPOLY corners.  A triangle cut by six planes has at most nine in
+ * exact arithmetic; rounding can make a polygon slightly non-convex, which bounds the growth per
+ * plane by 4/3 (3, 4, 5, 6, 8, 10, 13).  Should a polygon ever need more, the oracle does not guess:
+ * it counts the event, drops the triangle, and the render call reports failure. */
+static int g_poly_overflow = 0; /* polygons that did not fit, since the last oracle_clip_stats(…, reset) */
+static int g_poly_max = 0;      /* largest corner count any clipped polygon reached */
+
+void oracle_clip_stats(int *overflows, int *max_corners, int reset)
+{
+    if (overflows) *overflows = g_poly_overflow;
+    if (max_corners) *max_corners = g_poly_max;
+    if (reset) { g_poly_overflow = 0; g_poly_max = 0; }
+}
+
 /* N2 + N3.  Returns the polygon's vertex count (0 = dropped). */
 static int clip_triangle(const overt tri[3], overt *poly)
 {
@@ -128,6 +142,11 @@ static int clip_triangle(const overt tri[3], overt *poly)
             const overt *p = &cur[(i + n - 1) % n];
             int cin = plane_dist(c, k) >= 0.0f;
             int pin = plane_dist(p, k) >= 0.0f;
+            if (m + 2 > MAXPOLY && (cin || pin)) { /* no room for what this corner may add */
+#pragma omp atomic
+                g_poly_overflow += 1;
+                return 0;
+            }
             if (cin) {
                 if (!pin) intersect(c, p, k, &nxt[m++]);
                 nxt[m++] = *c;
@@ -136,6 +155,10 @@ static int clip_triangle(const overt tri[3], overt *poly)
             }
         }
         n = m;
+        if (n > g_poly_max) {
+#pragma omp critical(oracle_poly_max)
+            if (n > g_poly_max) g_poly_max = n;
+        }
         overt *t = cur; cur = nxt; nxt = t;
         if (n < 3) return 0;
     }
@@ -368,6 +391,7 @@ int oracle_render_textured(const float *verts, uint32_t V, const uint32_t *idx, 
     (void)V;
     otexture *tex = (uvs && texels) ? build_pyramid(texels, tex_w, tex_h) : NULL;
     int used = 1;
+    const int overflow_before = g_poly_overflow;
 #ifdef _OPENMP
     if (nthreads <= 0) nthreads = omp_get_num_procs();
     used = nthreads;
@@ -403,7 +427,31 @@ int oracle_render_textured(const float *verts, uint32_t V, const uint32_t *idx, 
         free(f.key);
     }
     free_pyramid(tex);
+    if (g_poly_overflow != overflow_before) return -1; /* a clipped polygon outgrew MAXPOLY: the frames are not to be trusted */
     return used;
+}
+
+/* Supersampled output (the paper renders at a higher resolution and downsamples, Sec. 4.1 and
+ * appendix): the 2H x 2W frame `depth` (and optionally `rgb`) is averaged over 2x2 blocks.
+ * Depth: ((d00 + d01) + (d10 + d11)) * 0.25 in float32, in that order, background samples counting
+ * with the value the frame holds for them.  Colour: (a + b + c + d + 2) >> 2 per channel.
+ *   depth [B][2H][2W] float32 -> out_depth [B][H][W];  rgb [B][2H][2W][3] uint8 -> out_rgb [B][H][W][3] (both or neither) */
+void oracle_downsample2(const float *depth, const uint8_t *rgb, uint32_t B, int H, int W, float *out_depth, uint8_t *out_rgb)
+{
+    const size_t W2 = 2 * (size_t)W, H2 = 2 * (size_t)H;
+    for (uint32_t b = 0; b < B; ++b)
+        for (int y = 0; y < H; ++y)
+            for (int x = 0; x < W; ++x) {
+                const size_t s = (size_t)b * H2 * W2 + (size_t)(2 * y) * W2 + (size_t)(2 * x);
+                const float top = depth[s] + depth[s + 1];
+                const float bottom = depth[s + W2] + depth[s + W2 + 1];
+                out_depth[((size_t)b * H + y) * W + x] = (top + bottom) * 0.25f;
+                if (rgb && out_rgb)
+                    for (int c = 0; c < 3; ++c) {
+                        const int sum = rgb[3 * s + c] + rgb[3 * (s + 1) + c] + rgb[3 * (s + W2) + c] + rgb[3 * (s + W2 + 1) + c];
+                        out_rgb[(((size_t)b * H + y) * W + x) * 3 + c] = (uint8_t)((sum + 2) >> 2);
+                    }
+            }
 }
 
 /* N10 alone: the texel the sampling rule picks for (u, v) at mip level L. */

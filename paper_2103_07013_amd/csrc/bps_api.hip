@@ -61,6 +61,7 @@ struct Retired {      // device block or table slot that queued requests may sti
     Arena arena;
     int slot = -1;
     uint64_t last_use = 0;
+    hipEvent_t upload = nullptr;   // the scene's own upload, if it was still in flight when the scene was retired
 };
 
 struct Staging {      // pinned host image of a scene being copied
@@ -96,7 +97,9 @@ struct bps_renderer {
     size_t lds = 0;
     size_t max_lds = 0;
     std::string error = "";
+    std::mutex err_mu;                // guards `error` alone (failures are also reported from outside `mu`)
     std::vector<HostScene> scenes;
+    std::vector<uint32_t> gens;       // generation of every table slot: part of the handle, so that a stale handle is refused
     std::vector<Retired> retired;     // waiting for the requests that used them
     std::vector<Arena> arena_pool;    // free device blocks, reused by later loads
     std::vector<Staging> staging;     // pinned images, reused once their copy has finished
@@ -125,6 +128,7 @@ struct bps_renderer {
     int plan_splits = 0;
     uint64_t plan_version = 0;        // counts the plans made; ring slots remember which one they hold
     std::vector<bps::WorkItem> plan_items;
+    std::vector<bps_scene> call_slots;    // table slots of the current request's scene handles (keeps its capacity)
     uint64_t last_splits = 0, last_groups = 0;
     unsigned char* static_scratch = nullptr;   // this device's copy of the static scratch array (bps_render_static)
     // last request that used a buffer every request shares (ids, gvis, ss_*, d_stats): a later one on
@@ -141,7 +145,12 @@ bps_status fail(bps_renderer* r, bps_status code, const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(buf, sizeof(buf), fmt, ap);
     va_end(ap);
-    if (r) r->error = buf; else g_create_error = buf;
+    if (r) {
+        std::lock_guard<std::mutex> g(r->err_mu);
+        r->error = buf;
+    } else {
+        g_create_error = buf;
+    }
     return code;
 }
 
@@ -152,6 +161,18 @@ bps_status fail(bps_renderer* r, bps_status code, const char* fmt, ...) {
             return fail((r), e_ == hipErrorOutOfMemory ? BPS_ERR_OOM : BPS_ERR_HIP, "%s: %s", \
                         #call, hipGetErrorString(e_));                                        \
     } while (0)
+
+// A scene handle is its table slot (low 12 bits) and the slot's generation at load time above it.
+constexpr int kSlotBits = 12;
+static_assert((1 << kSlotBits) == kMaxScenes, "a handle holds the table slot in its low bits");
+bps_scene make_handle(const bps_renderer* r, int slot) { return (bps_scene)((uint32_t)slot | (r->gens[slot] << kSlotBits)); }
+// Table slot of a live handle, -1 for anything else (never loaded, retired, or retired and the slot reused).
+int slot_of(const bps_renderer* r, bps_scene h) {
+    if (h < 0) return -1;
+    const size_t slot = (uint32_t)h & (uint32_t)(kMaxScenes - 1);
+    if (slot >= r->scenes.size() || !r->scenes[slot].live || r->gens[slot] != ((uint32_t)h >> kSlotBits)) return -1;
+    return (int)slot;
+}
 
 void free_scene(HostScene& s) {
     if (s.arena.ptr) (void)hipFree(s.arena.ptr);
@@ -175,7 +196,13 @@ void collect(bps_renderer* r) {
     (void)hipGetLastError();
     note_completions(r);
     for (size_t i = 0; i < r->retired.size();) {
-        if (r->retired[i].last_use <= r->done_seq) {
+        Retired& x = r->retired[i];
+        if (x.upload && hipEventQuery(x.upload) == hipSuccess) {
+            (void)hipEventDestroy(x.upload);
+            x.upload = nullptr;
+        }
+        (void)hipGetLastError();
+        if (x.last_use <= r->done_seq && !x.upload) {
             if (r->retired[i].arena.ptr) r->arena_pool.push_back(r->retired[i].arena);
             r->retired[i] = r->retired.back();
             r->retired.pop_back();
@@ -270,7 +297,14 @@ bps::FrameParams frame_params(const bps_renderer* r, int S) {
 
 extern "C" {
 
-const char* bps_last_error(const bps_renderer* r) { return r ? r->error.c_str() : g_create_error.c_str(); }
+const char* bps_last_error(const bps_renderer* r) {
+    if (!r) return g_create_error.c_str();
+    // a copy per calling thread: another thread's failure cannot change the text while the caller reads it
+    thread_local std::string text;
+    std::lock_guard<std::mutex> g(const_cast<bps_renderer*>(r)->err_mu);
+    text = r->error;
+    return text.c_str();
+}
 
 bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
     if (!cfg || !out) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: null argument");
@@ -286,7 +320,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown mode %d", cfg->mode);
     if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 384 && cfg->threads != 512 && cfg->threads != 1024)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 384, 512 or 1024");
-    if (cfg->splits < 0) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be >= 0");
+    if (cfg->splits < 0 || cfg->splits > 0xFFFF) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be 0..65535");
     if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL | BPS_FLAG_NO_DISPATCH_ORDER | BPS_FLAG_INPUTS_READY)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
@@ -384,8 +418,10 @@ void bps_destroy(bps_renderer* r) {
     (void)hipSetDevice(r->device);
     (void)hipDeviceSynchronize();
     for (HostScene& s : r->scenes) free_scene(s);
-    for (Retired& x : r->retired)
+    for (Retired& x : r->retired) {
         if (x.arena.ptr) (void)hipFree(x.arena.ptr);
+        if (x.upload) (void)hipEventDestroy(x.upload);
+    }
     for (Arena& x : r->arena_pool) (void)hipFree(x.ptr);
     for (Staging& x : r->staging) {
         (void)hipHostFree(x.ptr);
@@ -445,7 +481,8 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
     } catch (const std::bad_alloc&) {
         return fail(r, BPS_ERR_OOM, "bps_load_scene: out of host memory while clustering");
     }
-    if (cs.count == 0 || cs.count >= (1u << 24)) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: unsupported cluster count %u", cs.count);
+    // (the raster kernel's survivor records keep 23 bits for the cluster)
+    if (cs.count == 0 || cs.count >= (1u << 23)) return fail(r, BPS_ERR_INVALID_ARG, "bps_load_scene: unsupported cluster count %u", cs.count);
 
     // ---- layout of the block (every array 256-byte aligned), scene-table record last
     const uint32_t c_stride = (cs.count + 63u) & ~63u, nblocks = c_stride / 64u;
@@ -557,6 +594,7 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
         }
         slot = (int)r->scenes.size();
         r->scenes.emplace_back();
+        r->gens.push_back(0u);
     }
     Arena arena;
     int best = -1;
@@ -626,7 +664,7 @@ bps_status load_scene_on(bps_renderer* r, const float* vertices, uint32_t V, con
     hs.live = true;
     r->scenes[slot] = hs;
     r->plan_ids.clear();
-    *out_handle = slot;
+    *out_handle = make_handle(r, slot);
     return BPS_OK;
 }
 
@@ -639,7 +677,9 @@ bps_status bps_load_scene(bps_renderer* r, const float* vertices, uint32_t V, co
     if (st != BPS_OK) return st;
     BPS_HIP(r, hipStreamSynchronize(r->load_stream));
     std::lock_guard<std::mutex> lock(r->mu);
-    HostScene& hs = r->scenes[*out_handle];
+    const int slot = slot_of(r, *out_handle);
+    if (slot < 0) return BPS_OK;      // (another thread has retired it already)
+    HostScene& hs = r->scenes[slot];
     if (hs.ready) (void)hipEventDestroy(hs.ready);
     hs.ready = nullptr;
     return BPS_OK;
@@ -666,7 +706,9 @@ bps_status bps_load_scene_textured(bps_renderer* r, const float* vertices, uint3
     if (st != BPS_OK || copy_stream) return st;
     BPS_HIP(r, hipStreamSynchronize(r->load_stream));
     std::lock_guard<std::mutex> lock(r->mu);
-    HostScene& hs = r->scenes[*out_handle];
+    const int slot = slot_of(r, *out_handle);
+    if (slot < 0) return BPS_OK;      // (another thread has retired it already)
+    HostScene& hs = r->scenes[slot];
     if (hs.ready) (void)hipEventDestroy(hs.ready);
     hs.ready = nullptr;
     return BPS_OK;
@@ -675,9 +717,9 @@ bps_status bps_load_scene_textured(bps_renderer* r, const float* vertices, uint3
 bps_status bps_scene_ready(bps_renderer* r, bps_scene scene, int32_t* ready) {
     if (!r || !ready) return BPS_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lock(r->mu);
-    if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
-        return fail(r, BPS_ERR_BAD_HANDLE, "bps_scene_ready: scene %d is not loaded", scene);
-    HostScene& hs = r->scenes[scene];
+    const int slot = slot_of(r, scene);
+    if (slot < 0) return fail(r, BPS_ERR_BAD_HANDLE, "bps_scene_ready: scene %d is not loaded", scene);
+    HostScene& hs = r->scenes[slot];
     if (hs.ready && hipEventQuery(hs.ready) == hipSuccess) {
         (void)hipEventDestroy(hs.ready);
         hs.ready = nullptr;
@@ -711,22 +753,20 @@ bps_status bps_pack_clusters(const float* vertices, uint32_t V, const uint32_t* 
 bps_status bps_unload_scene(bps_renderer* r, bps_scene scene) {
     if (!r) return BPS_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lock(r->mu);
-    if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
-        return fail(r, BPS_ERR_BAD_HANDLE, "bps_unload_scene: scene %d is not loaded", scene);
+    const int slot = slot_of(r, scene);
+    if (slot < 0) return fail(r, BPS_ERR_BAD_HANDLE, "bps_unload_scene: scene %d is not loaded", scene);
     BPS_HIP(r, hipSetDevice(r->device));
-    HostScene& hs = r->scenes[scene];
-    if (hs.ready) {   // the upload itself must be over before the block can be reused
-        BPS_HIP(r, hipEventSynchronize(hs.ready));
-        (void)hipEventDestroy(hs.ready);
-        hs.ready = nullptr;
-    }
-    // queued requests may still read the block and the table slot: park both until they are done
+    HostScene& hs = r->scenes[slot];
+    // queued requests may still read the block and the table slot, and the scene's own upload may
+    // still be writing it: park both until all of that is over (nothing here waits for the device)
     Retired x;
     x.arena = hs.arena;
-    x.slot = scene;
+    x.slot = slot;
     x.last_use = hs.last_use;
+    x.upload = hs.ready;
     r->retired.push_back(x);
     hs = HostScene{};
+    r->gens[slot] = (r->gens[slot] + 1u) & ((1u << (31 - kSlotBits)) - 1u);      // handles to the old scene stop matching
     r->plan_ids.clear();
     collect(r);
     return BPS_OK;
@@ -744,14 +784,16 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     if (rgbd && !out_rgb) return fail(r, BPS_ERR_INVALID_ARG, "bps_render: out_rgb is required in RGB-D mode");
     hipStream_t stream = (hipStream_t)stream_;
     uint32_t min_clusters = 0xFFFFFFFFu;
+    r->call_slots.resize(B);
     for (uint32_t b = 0; b < B; ++b) {
-        bps_scene s = scene_ids[b];
-        if (s < 0 || (size_t)s >= r->scenes.size() || !r->scenes[s].live)
-            return fail(r, BPS_ERR_BAD_HANDLE, "bps_render: scene_ids[%u]=%d is not a loaded scene", b, s);
+        const int s = slot_of(r, scene_ids[b]);
+        if (s < 0) return fail(r, BPS_ERR_BAD_HANDLE, "bps_render: scene_ids[%u]=%d is not a loaded scene", b, scene_ids[b]);
         if (rgbd && !r->scenes[s].has_colors)
-            return fail(r, BPS_ERR_INVALID_ARG, "bps_render: scene %d (scene_ids[%u]) was loaded without colours", s, b);
+            return fail(r, BPS_ERR_INVALID_ARG, "bps_render: scene %d (scene_ids[%u]) was loaded without colours", scene_ids[b], b);
         min_clusters = std::min(min_clusters, r->scenes[s].dev.n_clusters);
+        r->call_slots[b] = s;
     }
+    scene_ids = r->call_slots.data();      // table slots from here on
     BPS_HIP(r, hipSetDevice(r->device));
     const uint64_t seq = ++r->seq;
     std::vector<hipEvent_t> uploads_pending;      // asynchronous scene uploads this request has to follow
@@ -970,11 +1012,13 @@ bps_status bps_render_static(bps_renderer* r, const bps_scene* scene_ids, const 
     (void)hipGetLastError();
     if (!vp_on_device) return fail(r, BPS_ERR_INVALID_ARG, "bps_render_static: view_proj must be device memory");
     hipStream_t stream = (hipStream_t)stream_;
+    r->call_slots.resize(B);
     for (uint32_t b = 0; b < B; ++b) {
-        bps_scene s = scene_ids[b];
-        if (s < 0 || (size_t)s >= r->scenes.size() || !r->scenes[s].live)
-            return fail(r, BPS_ERR_BAD_HANDLE, "bps_render_static: scene_ids[%u]=%d is not a loaded scene", b, s);
+        const int s = slot_of(r, scene_ids[b]);
+        if (s < 0) return fail(r, BPS_ERR_BAD_HANDLE, "bps_render_static: scene_ids[%u]=%d is not a loaded scene", b, scene_ids[b]);
+        r->call_slots[b] = s;
     }
+    scene_ids = r->call_slots.data();      // table slots from here on
     BPS_HIP(r, hipSetDevice(r->device));
     const uint64_t seq = ++r->seq;
     for (uint32_t b = 0; b < B; ++b) {
@@ -1040,6 +1084,7 @@ bps_status bps_render_static(bps_renderer* r, const bps_scene* scene_ids, const 
 
 bps_status bps_set_profiling(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(r->mu);
     r->profiling = enable != 0;
     r->profile_every = enable > 1 ? (uint32_t)enable : 1u;
     r->profile_count = 0;
@@ -1084,6 +1129,7 @@ bps_status bps_kernel_ms_each(bps_renderer* r, float* out, uint32_t capacity, ui
 
 bps_status bps_set_diagnostics(bps_renderer* r, int32_t enable) {
     if (!r) return BPS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(r->mu);
     r->want_stats = enable != 0;
     r->stats_mode = enable > 1 ? (enable <= 4 ? enable - 1 : 1) : 0;
     return BPS_OK;
@@ -1102,10 +1148,11 @@ bps_status bps_read_diagnostics(bps_renderer* r, uint64_t* out, uint32_t capacit
 
 bps_status bps_query(bps_renderer* r, bps_scene scene, int32_t what, uint64_t* value) {
     if (!r || !value) return BPS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(r->mu);
     if (what >= 0 && what <= 3) {
-        if (scene < 0 || (size_t)scene >= r->scenes.size() || !r->scenes[scene].live)
-            return fail(r, BPS_ERR_BAD_HANDLE, "bps_query: scene %d is not loaded", scene);
-        const HostScene& s = r->scenes[scene];
+        const int slot = slot_of(r, scene);
+        if (slot < 0) return fail(r, BPS_ERR_BAD_HANDLE, "bps_query: scene %d is not loaded", scene);
+        const HostScene& s = r->scenes[slot];
         *value = what == 0 ? s.dev.n_clusters : what == 1 ? s.dev.n_tris : what == 2 ? s.dev.n_verts : s.bytes;
         return BPS_OK;
     }

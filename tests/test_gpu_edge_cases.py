@@ -183,6 +183,75 @@ def test_asynchronous_scene_rotation_while_rendering():
         assert bps.bps_query(r.handle, 0, 8) <= 4          # blocks were reused, not allocated per load
 
 
+def test_loader_thread_rotates_scenes_beside_the_render_thread():
+    """The paper's asynchronous asset loading with real threads: a loader thread keeps replacing the
+    resident scenes (asynchronous upload on its own stream, retirement of the scene it replaces) while
+    the main thread issues render requests without ever synchronising.  Every frame of every request
+    is checked against the oracle for the scenes that request named."""
+    import threading
+    import torch
+    import oracle
+    import paper_2103_07013_amd as bps
+    meshes = [synth.make_multiroom_scene(20_000, seed=1200 + k) for k in range(7)]
+    cams = [synth.make_cameras(m, 8, seed=91 + k)[0] for k, m in enumerate(meshes)]
+    refs = [oracle.render_scene(m.vertices, m.indices, cams[k], 64, 64) for k, m in enumerate(meshes)]
+    K, want_sets, max_requests = 3, 5, 6000
+    ref_d = torch.from_numpy(np.stack([x["depth"] for x in refs])).cuda()                      # [mesh, 8, H, W]
+    ref_t = torch.from_numpy(np.stack([x["tri_id"] for x in refs]).view(np.int32)).cuda()
+    copy_stream = torch.cuda.Stream()
+    with bps.Renderer(max_batch=8 * K) as r:
+        lock = threading.Lock()
+        state = {"mesh": [0, 1, 2], "stop": False, "swaps": 0, "error": None}
+        state["handle"] = [r.load_scene(meshes[k].vertices, meshes[k].indices) for k in state["mesh"]]
+
+        def loader():
+            try:
+                n = 0
+                while not state["stop"]:
+                    slot, mesh = n % K, (n + K) % len(meshes)
+                    n += 1
+                    if mesh in state["mesh"]:
+                        continue
+                    new = bps.bps_load_scene_async(r.handle, meshes[mesh].vertices, meshes[mesh].indices, None, copy_stream)
+                    with lock:      # the render thread names scenes and submits under the same lock
+                        old = state["handle"][slot]
+                        state["handle"][slot], state["mesh"][slot] = new, mesh
+                        bps.bps_unload_scene(r.handle, old)      # requests that use it may still be queued
+                    state["swaps"] += 1
+            except Exception as e:      # surfaces in the main thread's assert
+                state["error"] = e
+
+        th = threading.Thread(target=loader)
+        th.start()
+        # expected frames per set of resident meshes, put together on the device (no host round trip per
+        # request: the render thread never waits for the GPU while the loader runs)
+        expected = {}
+        wrong = torch.zeros((), dtype=torch.int64, device="cuda")
+        depth = [torch.empty((8 * K, 64, 64), dtype=torch.float32, device="cuda") for _ in range(2)]
+        tid = [torch.empty((8 * K, 64, 64), dtype=torch.int32, device="cuda") for _ in range(2)]
+        issued, sets_seen = 0, set()
+        try:
+            while len(sets_seen) < want_sets and issued < max_requests and state["error"] is None:
+                with lock:
+                    used = tuple(state["mesh"])
+                    ids = np.repeat(np.array(state["handle"], np.int32), 8)
+                    vp = np.concatenate([cams[m] for m in used])
+                    bps.bps_render(r.handle, ids, vp, depth[issued & 1], out_tri_id=tid[issued & 1])   # not synchronised
+                if used not in expected:
+                    expected[used] = (torch.cat([ref_d[m] for m in used]), torch.cat([ref_t[m] for m in used]))
+                wrong += (depth[issued & 1] != expected[used][0]).sum() + (tid[issued & 1] != expected[used][1]).sum()
+                sets_seen.add(used)
+                issued += 1
+        finally:
+            state["stop"] = True
+            th.join()
+        torch.cuda.synchronize()
+        assert state["error"] is None, state["error"]
+        assert len(sets_seen) >= want_sets, "the requests did not get to see scenes being replaced"
+        assert state["swaps"] >= want_sets - 1 and issued >= want_sets
+        assert int(wrong.item()) == 0, f"{int(wrong.item())} pixels of {issued} requests differ from the oracle"
+
+
 @pytest.mark.parametrize("rgbd", [False, True])
 def test_requests_in_flight_on_two_streams(rgbd):
     """Consecutive requests on two alternating streams may overlap on the device.  Every frame must
@@ -251,3 +320,40 @@ def test_requests_planned_on_the_renderers_own_stream(device_matrices):
         torch.cuda.synchronize()
         for step, (k, n, depth) in enumerate(outs):
             assert np.array_equal(depth.cpu().numpy(), refs[k]["depth"][:n]), f"request {step}"
+
+
+def test_stale_scene_handles_are_refused_after_their_slot_is_reused(room):
+    """A handle names one load.  After bps_unload_scene it is refused, also once a later scene has taken
+    its table slot (the new scene gets a different handle), and retiring a scene whose asynchronous
+    upload has only just been enqueued does not wait and does not break later loads."""
+    import torch
+    import paper_2103_07013_amd as bps
+    w = room
+    s = w.scenes[0]
+    small = synth.make_room_scene(2_000, seed=5)
+    copy_stream = torch.cuda.Stream()
+    with bps.Renderer(max_batch=4) as r:
+        first = r.load_scene(s.vertices, s.indices)
+        r.unload_scene(first)
+        torch.cuda.synchronize()
+        second = r.load_scene(small.vertices, small.indices)          # takes the free slot
+        assert second != first
+        for stale_call in (lambda: r.render(np.full(4, first, np.int32), w.view_proj[:4]),
+                           lambda: bps.bps_unload_scene(r.handle, first),
+                           lambda: bps.bps_scene_ready(r.handle, first),
+                           lambda: bps.bps_query(r.handle, first, 1)):
+            with pytest.raises(bps.BpsError) as e:
+                stale_call()
+            assert e.value.status == -2
+        assert bps.bps_query(r.handle, second, 1) == small.T
+        # retire a scene right after enqueuing its upload, then keep loading and rendering
+        for k in range(4):
+            h = bps.bps_load_scene_async(r.handle, s.vertices, s.indices, None, copy_stream)
+            bps.bps_unload_scene(r.handle, h)
+        h = bps.bps_load_scene_async(r.handle, s.vertices, s.indices, None, copy_stream)
+        depth, _, tid = r.render(np.full(4, h, np.int32), w.view_proj[:4], want_tri_id=True)
+        torch.cuda.synchronize()
+        import oracle
+        ref = oracle.render_scene(s.vertices, s.indices, w.view_proj[:4], 64, 64)
+        assert np.array_equal(tid.cpu().numpy().view(np.uint32), ref["tri_id"])
+        assert np.array_equal(depth.cpu().numpy(), ref["depth"])

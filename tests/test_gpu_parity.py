@@ -161,16 +161,15 @@ def test_frames_cut_into_tiles_match_oracle(H, W):
 @pytest.mark.parametrize("rgbd", [False, True])
 def test_supersampled_output_is_the_box_filter_of_the_double_resolution_render(rgbd):
     """Render at 2H x 2W and average 2x2 blocks (the paper's 256 -> 128 downsampling, at the sizes
-    this library supports).  Expected values: the oracle's double-resolution frames, filtered here
-    with the documented operation order."""
+    this library supports).  Expected values: the oracle's double-resolution frames through the
+    oracle's own box filter."""
     import torch
     import oracle
     import paper_2103_07013_amd as bps
     w = synth.build_config(4 if rgbd else 2, B=8, scale=0.05 if rgbd else 0.2)
     H = W = 48
     ref = oracle.render_batch(w.scenes, w.scene_ids, w.view_proj, 2 * H, 2 * W, rgbd=rgbd)
-    d = ref["depth"]
-    expect = ((d[:, 0::2, 0::2] + d[:, 0::2, 1::2]) + (d[:, 1::2, 0::2] + d[:, 1::2, 1::2])) * np.float32(0.25)
+    expect, expect_rgb = oracle.downsample2(ref["depth"], ref["rgb"] if rgbd else None)
     with bps.Renderer(max_batch=w.B, height=H, width=W, supersample=2,
                       mode=bps.MODE_RGBD if rgbd else bps.MODE_DEPTH) as r:
         hs = [r.load_scene(s.vertices, s.indices, s.colors if rgbd else None) for s in w.scenes]
@@ -180,9 +179,7 @@ def test_supersampled_output_is_the_box_filter_of_the_double_resolution_render(r
         assert tuple(depth.shape) == (w.B, H, W)
         assert np.array_equal(depth.cpu().numpy(), expect)
         if rgbd:
-            c = ref["rgb"].astype(np.int32)
-            ec = (c[:, 0::2, 0::2] + c[:, 0::2, 1::2] + c[:, 1::2, 0::2] + c[:, 1::2, 1::2] + 2) >> 2
-            assert np.array_equal(rgb.cpu().numpy().astype(np.int32), ec)
+            assert np.array_equal(rgb.cpu().numpy(), expect_rgb)
         with pytest.raises(bps.BpsError):
             r.render(ids, w.view_proj, want_tri_id=True)
 

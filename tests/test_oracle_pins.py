@@ -681,3 +681,45 @@ def test_mip_level_uses_the_uv_area_of_a_sheared_mapping():
     expect = tex[np.minimum(ty.astype(int), W - 1), np.minimum(tx.astype(int), W - 1)]
     assert safe.mean() > 0.9
     assert np.array_equal(r["rgb"][0][safe], expect[safe])
+
+
+# ---------------------------------------------------------------- supersampled output and the clipper's capacity
+
+def test_box_filter_hand_computed_block_and_constant_plane():
+    """2x2 box filter of supersampled frames: one block worked out by hand (a background sample
+    counts with the frame's background value; the sum is taken pairwise, rows first), a constant
+    frame stays what it is, colours round half up."""
+    d = np.zeros((1, 4, 4), np.float32)
+    d[0, 0:2, 0:2] = [[1.5, 2.5], [0.0, 4.0]]                 # 0.0 = a background sample
+    d[0, 0:2, 2:4] = [[np.float32(1e8), 1.0], [-np.float32(1e8), 1.0]]   # order matters: (1e8 + 1) + (-1e8 + 1) = 0 in float32
+    d[0, 2:4, :] = 7.25
+    c = np.zeros((1, 4, 4, 3), np.uint8)
+    c[0, 0:2, 0:2, 0] = [[1, 2], [3, 4]]                      # 10 + 2 >> 2 = 3
+    c[0, 0:2, 0:2, 1] = [[255, 255], [255, 254]]              # 1019 + 2 >> 2 = 255
+    c[0, 0:2, 0:2, 2] = [[0, 0], [0, 1]]                      # 1 + 2 >> 2 = 0
+    od, oc = oracle.downsample2(d, c)
+    assert od.shape == (1, 2, 2) and oc.shape == (1, 2, 2, 3)
+    assert od[0, 0, 0] == np.float32(2.0)                     # (1.5 + 2.5) + (0 + 4) = 8, / 4
+    assert od[0, 0, 1] == np.float32(0.0)                     # both row sums round to +-1e8
+    assert od[0, 1, 0] == np.float32(7.25) and od[0, 1, 1] == np.float32(7.25)
+    assert tuple(oc[0, 0, 0]) == (3, 255, 0)
+    assert np.all(oc[0, 1] == 0)
+    plane = np.full((3, 16, 24), 3.375, np.float32)
+    assert np.all(oracle.downsample2(plane)[0] == np.float32(3.375))
+
+
+def test_clipper_capacity_is_never_reached_and_is_reported_if_it_were():
+    """Clip-heavy random soups, cameras inside the geometry: the largest polygon the clipper ever
+    builds stays well below its 16 corners (nine in exact arithmetic), and no polygon is dropped
+    for lack of room.  Every render call would fail loudly otherwise."""
+    oracle.clip_stats(reset=True)
+    for seed in range(6):
+        rng = np.random.default_rng(100 + seed)
+        v, idx = random_soup(rng, 400, spread=2.0, zmin=-3.0, zmax=2.0, size=4.0)
+        M = cam(pos=(0.1 * seed, -0.2, 0.5), yaw=0.7 * seed, pitch=0.3 * (seed - 3), near=0.05, far=6.0)
+        oracle.render_scene(v, idx, M[None], 32, 32)
+    w = synth.build_config(2, B=6, scale=0.02)
+    oracle.render_batch(w.scenes, w.scene_ids, w.view_proj, 64, 64)
+    overflows, largest = oracle.clip_stats()
+    assert overflows == 0
+    assert 7 <= largest <= 10, largest          # six planes cut: up to nine corners, one more through rounding at most
