@@ -58,6 +58,9 @@ enum {
                                        them): staging and launch planning may then start at once, on a stream
                                        of the renderer, instead of queuing behind the caller's stream.  Host
                                        arrays are consumed during the call and always get this treatment. */
+    ,
+    BPS_FLAG_BILINEAR = 16          /* textured scenes: blend the four texels around the sample position
+                                       (see bps_load_scene_textured) instead of taking the nearest one */
 };
 
 typedef struct {
@@ -115,7 +118,11 @@ bps_status bps_scene_ready(bps_renderer *r, bps_scene scene, int32_t *ready);
  * perspective-correctly like colours; the library builds a mip pyramid (each level halves both
  * sides, a texel is (a+b+c+d+2)>>2 of its 2x2 parents); each rasterised triangle uses the level
  * at which one pixel covers fewer than four texels (from its uv area and pixel area); the texel
- * is the one containing (u - floor u, v - floor v).  copy_stream NULL = wait for the upload,
+ * is the one containing (u - floor u, v - floor v).  With BPS_FLAG_BILINEAR the four texels of
+ * that level around the sample position are blended instead: x = fu lw - 0.5, x0 = floor x,
+ * tx = x - x0, texels x0 and x0 + 1 wrapped around the texture's sides (likewise y), per channel
+ * top = fma(tx, c01 - c00, c00), bot = fma(tx, c11 - c10, c10), out = rint(fma(ty, bot - top, top))
+ * in float32, so colours stay reproducible bit for bit.  copy_stream NULL = wait for the upload,
  * otherwise the copy is only enqueued there (see bps_load_scene_async). */
 bps_status bps_load_scene_textured(bps_renderer *r, const float *vertices, uint32_t V, const uint32_t *indices,
                                    uint32_t T, const float *uvs, const uint8_t *texels, uint32_t tex_w,

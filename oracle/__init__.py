@@ -42,6 +42,13 @@ def _load():
         lib.oracle_render_textured.argtypes = [f32p, ctypes.c_uint32, u32p, ctypes.c_uint32, u8p, f32p, u8p, ctypes.c_int,
                                                ctypes.c_int, f32p, ctypes.c_uint32, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_float, f32p, u32p, u8p, u32p, ctypes.c_int]
+        lib.oracle_render_filtered.restype = ctypes.c_int
+        lib.oracle_render_filtered.argtypes = [f32p, ctypes.c_uint32, u32p, ctypes.c_uint32, u8p, f32p, u8p, ctypes.c_int,
+                                               ctypes.c_int, ctypes.c_int, f32p, ctypes.c_uint32, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_float, f32p, u32p, u8p, u32p, ctypes.c_int]
+        lib.oracle_sample_filtered.restype = None
+        lib.oracle_sample_filtered.argtypes = [u8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_float,
+                                               ctypes.c_int, u8p]
         lib.oracle_sample.restype = None
         lib.oracle_sample.argtypes = [u8p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_float, u8p]
         lib.oracle_cover_fixed.restype = None
@@ -61,9 +68,9 @@ def _p(a, t):
 
 
 def render_scene(vertices, indices, view_proj, H, W, colors=None, background=0.0, want_cover=False, nthreads=0,
-                 uvs=None, texture=None):
+                 uvs=None, texture=None, bilinear=False):
     """Render every matrix in view_proj[B,4,4] against one mesh.  With uvs [V,2] and texture
-    [th,tw,3] uint8 the colour output is sampled from the texture (rule N10).
+    [th,tw,3] uint8 the colour output is sampled from the texture (rule N10, or N11 with bilinear).
 
     Returns dict(depth f32 [B,H,W], tri_id u32 [B,H,W], rgb u8 [B,H,W,3] | None,
     cover u32 [B,H,W] | None, threads int)."""
@@ -83,10 +90,10 @@ def render_scene(vertices, indices, view_proj, H, W, colors=None, background=0.0
     tid = np.empty((B, H, W), np.uint32)
     rgb = np.zeros((B, H, W, 3), np.uint8) if (c is not None or tex is not None) else None
     cover = np.zeros((B, H, W), np.uint32) if want_cover else None
-    used = lib.oracle_render_textured(_p(v, ctypes.c_float), v.shape[0], _p(i, ctypes.c_uint32), i.shape[0],
+    used = lib.oracle_render_filtered(_p(v, ctypes.c_float), v.shape[0], _p(i, ctypes.c_uint32), i.shape[0],
                                       _p(c, ctypes.c_uint8), _p(uv, ctypes.c_float), _p(tex, ctypes.c_uint8),
                                       0 if tex is None else tex.shape[1], 0 if tex is None else tex.shape[0],
-                                      _p(m, ctypes.c_float), B, H, W, float(background),
+                                      1 if bilinear else 0, _p(m, ctypes.c_float), B, H, W, float(background),
                                       _p(depth, ctypes.c_float), _p(tid, ctypes.c_uint32), _p(rgb, ctypes.c_uint8),
                                       _p(cover, ctypes.c_uint32), int(nthreads))
     if used < 0:
@@ -117,7 +124,7 @@ def downsample2(depth, rgb=None):
 
 
 def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0, nthreads=0, want_cover=False,
-                 textured=False):
+                 textured=False, bilinear=False):
     """Render a mixed batch: env b uses scenes[scene_ids[b]] (objects with .vertices/.indices/.colors,
     and .uvs/.texture when textured)."""
     scene_ids = np.asarray(scene_ids)
@@ -132,7 +139,7 @@ def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0,
         s = scenes[int(k)]
         r = render_scene(s.vertices, s.indices, view_proj[sel], H, W, colors=s.colors if (rgbd and not textured) else None,
                          background=background, nthreads=nthreads, want_cover=want_cover,
-                         uvs=s.uvs if textured else None, texture=s.texture if textured else None)
+                         uvs=s.uvs if textured else None, texture=s.texture if textured else None, bilinear=bilinear)
         depth[sel], tid[sel] = r["depth"], r["tri_id"]
         if rgbd:
             rgb[sel] = r["rgb"]
@@ -142,12 +149,13 @@ def render_batch(scenes, scene_ids, view_proj, H, W, rgbd=False, background=0.0,
     return dict(depth=depth, tri_id=tid, rgb=rgb, cover=cover, threads=threads)
 
 
-def sample(texture, level, u, v):
-    """The RGB texel rule N10 picks for (u, v) at mip level `level`."""
+def sample(texture, level, u, v, bilinear=False):
+    """The RGB colour rule N10 (nearest texel) or N11 (bilinear) gives for (u, v) at mip level `level`."""
     lib = _load()
     tex = np.ascontiguousarray(texture, np.uint8)
     out = np.zeros(3, np.uint8)
-    lib.oracle_sample(_p(tex, ctypes.c_uint8), tex.shape[1], tex.shape[0], int(level), float(u), float(v), _p(out, ctypes.c_uint8))
+    lib.oracle_sample_filtered(_p(tex, ctypes.c_uint8), tex.shape[1], tex.shape[0], int(level), float(u), float(v),
+                               1 if bilinear else 0, _p(out, ctypes.c_uint8))
     return out
 
 

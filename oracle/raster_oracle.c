@@ -41,6 +41,11 @@
  *       pixel), level = number of times r can be quartered while r >= 4 (at most the last level).
  *       Sample: fu = u - floor(u) (0 if that is not in [0,1)), x = min((int)(fu*lw), lw-1), likewise y;
  *       the pixel takes that texel, no filtering.
+ *   N11 bilinear filtering (optional; same level L and fractions fu, fv as N10): x = fu*lw - 0.5,
+ *       x0 = floor(x), tx = x - x0, x1 = x0 + 1, both wrapped into [0, lw) (the texture repeats;
+ *       sides are powers of two); likewise y.  Per channel, with the four texels as floats:
+ *       top = fma(tx, c01 - c00, c00), bot = fma(tx, c11 - c10, c10), v = fma(ty, bot - top, top),
+ *       out = clamp(lrint(v), 0, 255).  At a texel centre the result is that texel.
  *
  * Everything after N4 is exact integer arithmetic in int64.
  */
@@ -62,7 +67,36 @@ typedef struct {
 typedef struct {
     int w, h, levels;
     uint8_t **level; /* level[l] = RGB8 texels of size max(w>>l,1) x max(h>>l,1) */
+    int bilinear;    /* 0: N10 nearest texel, 1: N11 */
 } otexture;
+
+/* N10 / N11: the colour at fractions (fu, fv) in [0,1) of level L (lw x lh texels). */
+static void fetch_texel(const otexture *tx, int L, int lw, int lh, float fu, float fv, uint8_t *out)
+{
+    if (!tx->bilinear) {
+        int x = (int)(fu * (float)lw), y = (int)(fv * (float)lh);
+        if (x > lw - 1) x = lw - 1;
+        if (y > lh - 1) y = lh - 1;
+        memcpy(out, tx->level[L] + 3 * ((size_t)y * (size_t)lw + (size_t)x), 3);
+        return;
+    }
+    float x = fu * (float)lw - 0.5f, y = fv * (float)lh - 0.5f;
+    float fx0 = floorf(x), fy0 = floorf(y);
+    float tx_ = x - fx0, ty_ = y - fy0;
+    int x0 = (int)fx0 & (lw - 1), x1 = ((int)fx0 + 1) & (lw - 1); /* two's complement: -1 wraps to lw - 1 */
+    int y0 = (int)fy0 & (lh - 1), y1 = ((int)fy0 + 1) & (lh - 1);
+    const uint8_t *t = tx->level[L];
+    for (int c = 0; c < 3; ++c) {
+        float c00 = (float)t[3 * ((size_t)y0 * lw + x0) + c], c01 = (float)t[3 * ((size_t)y0 * lw + x1) + c];
+        float c10 = (float)t[3 * ((size_t)y1 * lw + x0) + c], c11 = (float)t[3 * ((size_t)y1 * lw + x1) + c];
+        float top = fmaf(tx_, c01 - c00, c00), bot = fmaf(tx_, c11 - c10, c10);
+        float v = fmaf(ty_, bot - top, top);
+        long q = lrintf(v);
+        if (q < 0) q = 0;
+        if (q > 255) q = 255;
+        out[c] = (uint8_t)q;
+    }
+}
 
 typedef struct {
     int H, W;
@@ -249,13 +283,7 @@ static void raster_subtri(oframe *f, const int64_t Xi[3], const int64_t Yi[3], c
                         if (!(fr >= 0.0f && fr < 1.0f)) fr = 0.0f;
                         uv[c] = fr;
                     }
-                    int x = (int)(uv[0] * (float)lw), y = (int)(uv[1] * (float)lh);
-                    if (x > lw - 1) x = lw - 1;
-                    if (y > lh - 1) y = lh - 1;
-                    const uint8_t *t = tx->level[L] + 3 * ((size_t)y * (size_t)lw + (size_t)x);
-                    f->rgb[p * 3 + 0] = t[0];
-                    f->rgb[p * 3 + 1] = t[1];
-                    f->rgb[p * 3 + 2] = t[2];
+                    fetch_texel(tx, L, lw, lh, uv[0], uv[1], f->rgb + p * 3);
                 } else if (f->rgb) {
                     for (int c = 0; c < 3; ++c) {
                         float cn = fmaf(e2 * iw[2], col[2][c], fmaf(e1 * iw[1], col[1][c], (e0 * iw[0]) * col[0][c]));
@@ -331,6 +359,7 @@ static otexture *build_pyramid(const uint8_t *texels, int w, int h)
     otexture *t = (otexture *)malloc(sizeof(otexture));
     t->w = w;
     t->h = h;
+    t->bilinear = 0;
     int levels = 1;
     for (int a = w, b = h; a > 1 || b > 1; a = a > 1 ? a / 2 : 1, b = b > 1 ? b / 2 : 1) ++levels;
     t->levels = levels;
@@ -372,6 +401,10 @@ int oracle_render_textured(const float *verts, uint32_t V, const uint32_t *idx, 
                            const float *uvs, const uint8_t *texels, int tex_w, int tex_h, const float *view_proj,
                            uint32_t B, int H, int W, float background, float *depth, uint32_t *tri_id, uint8_t *rgb,
                            uint32_t *cover, int nthreads);
+int oracle_render_filtered(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
+                           const float *uvs, const uint8_t *texels, int tex_w, int tex_h, int bilinear,
+                           const float *view_proj, uint32_t B, int H, int W, float background, float *depth,
+                           uint32_t *tri_id, uint8_t *rgb, uint32_t *cover, int nthreads);
 
 int oracle_render(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
                   const float *view_proj, uint32_t B, int H, int W, float background, float *depth,
@@ -388,8 +421,19 @@ int oracle_render_textured(const float *verts, uint32_t V, const uint32_t *idx, 
                            uint32_t B, int H, int W, float background, float *depth, uint32_t *tri_id, uint8_t *rgb,
                            uint32_t *cover, int nthreads)
 {
+    return oracle_render_filtered(verts, V, idx, T, colors, uvs, texels, tex_w, tex_h, 0, view_proj, B, H, W, background, depth,
+                                  tri_id, rgb, cover, nthreads);
+}
+
+/* As oracle_render_textured; bilinear = 1 samples the texture by rule N11 instead of N10. */
+int oracle_render_filtered(const float *verts, uint32_t V, const uint32_t *idx, uint32_t T, const uint8_t *colors,
+                           const float *uvs, const uint8_t *texels, int tex_w, int tex_h, int bilinear,
+                           const float *view_proj, uint32_t B, int H, int W, float background, float *depth,
+                           uint32_t *tri_id, uint8_t *rgb, uint32_t *cover, int nthreads)
+{
     (void)V;
     otexture *tex = (uvs && texels) ? build_pyramid(texels, tex_w, tex_h) : NULL;
+    if (tex) tex->bilinear = bilinear != 0;
     int used = 1;
     const int overflow_before = g_poly_overflow;
 #ifdef _OPENMP
@@ -454,10 +498,11 @@ void oracle_downsample2(const float *depth, const uint8_t *rgb, uint32_t B, int 
             }
 }
 
-/* N10 alone: the texel the sampling rule picks for (u, v) at mip level L. */
-void oracle_sample(const uint8_t *texels, int tex_w, int tex_h, int L, float u, float v, uint8_t *rgb_out)
+/* N10 / N11 alone: the colour the sampling rule gives for (u, v) at mip level L. */
+void oracle_sample_filtered(const uint8_t *texels, int tex_w, int tex_h, int L, float u, float v, int bilinear, uint8_t *rgb_out)
 {
     otexture *tx = build_pyramid(texels, tex_w, tex_h);
+    tx->bilinear = bilinear != 0;
     if (L > tx->levels - 1) L = tx->levels - 1;
     int lw = tx->w >> L, lh = tx->h >> L;
     if (lw < 1) lw = 1;
@@ -465,11 +510,13 @@ void oracle_sample(const uint8_t *texels, int tex_w, int tex_h, int L, float u, 
     float fu = u - floorf(u), fv = v - floorf(v);
     if (!(fu >= 0.0f && fu < 1.0f)) fu = 0.0f;
     if (!(fv >= 0.0f && fv < 1.0f)) fv = 0.0f;
-    int x = (int)(fu * (float)lw), y = (int)(fv * (float)lh);
-    if (x > lw - 1) x = lw - 1;
-    if (y > lh - 1) y = lh - 1;
-    memcpy(rgb_out, tx->level[L] + 3 * ((size_t)y * lw + x), 3);
+    fetch_texel(tx, L, lw, lh, fu, fv, rgb_out);
     free_pyramid(tx);
+}
+
+void oracle_sample(const uint8_t *texels, int tex_w, int tex_h, int L, float u, float v, uint8_t *rgb_out)
+{
+    oracle_sample_filtered(texels, tex_w, tex_h, L, u, v, 0, rgb_out);
 }
 
 /* N5-N6 alone: coverage counts of triangles given directly in 1/256-pixel integer

@@ -13,6 +13,7 @@ FLAG_NO_CLUSTER_CULL = 1
 FLAG_NO_OCCLUSION_CULL = 2
 FLAG_NO_DISPATCH_ORDER = 4
 FLAG_INPUTS_READY = 8
+FLAG_BILINEAR = 16
 EXPORTS = ["bps_create", "bps_destroy", "bps_load_scene", "bps_load_scene_async", "bps_load_scene_textured", "bps_scene_ready", "bps_pack_clusters", "bps_unload_scene", "bps_render", "bps_render_static", "bps_set_profiling",
            "bps_last_kernel_ms", "bps_kernel_ms_total", "bps_kernel_ms_each", "bps_set_diagnostics", "bps_read_diagnostics", "bps_query", "bps_last_error"]
 

@@ -290,6 +290,7 @@ bps::FrameParams frame_params(const bps_renderer* r, int S) {
     fp.round_target = r->round_target;
     fp.first_round = r->first_round;
     fp.phase_timers = r->want_stats ? r->stats_mode : 0;
+    fp.bilinear = (r->cfg.flags & BPS_FLAG_BILINEAR) ? 1 : 0;
     return fp;
 }
 
@@ -321,7 +322,7 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
     if (cfg->threads != 0 && cfg->threads != 256 && cfg->threads != 384 && cfg->threads != 512 && cfg->threads != 1024)
         return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: threads must be 0, 256, 384, 512 or 1024");
     if (cfg->splits < 0 || cfg->splits > 0xFFFF) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: splits must be 0..65535");
-    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL | BPS_FLAG_NO_DISPATCH_ORDER | BPS_FLAG_INPUTS_READY)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
+    if (cfg->flags & ~(uint32_t)(BPS_FLAG_NO_CLUSTER_CULL | BPS_FLAG_NO_OCCLUSION_CULL | BPS_FLAG_NO_DISPATCH_ORDER | BPS_FLAG_INPUTS_READY | BPS_FLAG_BILINEAR)) return fail(nullptr, BPS_ERR_INVALID_ARG, "bps_create: unknown flag bits 0x%x", cfg->flags);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
         return fail(nullptr, BPS_ERR_HIP, "bps_create: no HIP device available (this library has no CPU path)");

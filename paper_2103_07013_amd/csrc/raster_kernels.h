@@ -56,7 +56,8 @@ struct FrameParams {
     int32_t list_cap;      // capacity of the work-group's survivor list, in clusters
     int32_t round_target;  // survivors queued before a round's testing stops
     int32_t first_round;   // the same for an environment's first round (kept short when occlusion culling is on)
-    int32_t phase_timers;  // diagnostics: also time the kernel's phases (slows it down)
+    int32_t phase_timers;  // diagnostics: 1 also time the kernel's phases (slows it down), 2 / 3 path tallies
+    int32_t bilinear;      // colour pass: sample textures with bilinear filtering instead of the nearest texel
 };
 
 constexpr unsigned long long kEmptyKey = ~0ull;

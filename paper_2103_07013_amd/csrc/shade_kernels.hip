@@ -70,8 +70,8 @@ __device__ __forceinline__ uint8_t to_u8(float v) {
 }
 
 // Texel or interpolated colour of one covering fan piece (rgb holds (u, v, -) for textured scenes).
-__device__ __forceinline__ void piece_output(const SceneDev& sc, bool textured, const float (&rgb)[3], float uv_area2,
-                                             int area2, uint8_t (&out)[3]) {
+__device__ __forceinline__ void piece_output(const SceneDev& sc, bool textured, bool bilinear, const float (&rgb)[3],
+                                             float uv_area2, int area2, uint8_t (&out)[3]) {
     if (textured) {
         // mip level: quarter the texels-per-pixel ratio while it is at least 4
         float ratio = ((uv_area2 * (float)sc.tex_w) * (float)sc.tex_h) * 65536.0f / (float)area2;
@@ -87,6 +87,24 @@ __device__ __forceinline__ void piece_output(const SceneDev& sc, bool textured, 
         float fu = rgb[0] - floorf(rgb[0]), fv = rgb[1] - floorf(rgb[1]);
         if (!(fu >= 0.0f && fu < 1.0f)) fu = 0.0f;
         if (!(fv >= 0.0f && fv < 1.0f)) fv = 0.0f;
+        if (bilinear) {
+            // the four texels around the sample position, wrapped around the texture's (power-of-two) sides
+            const float x = fu * (float)lw - 0.5f, y = fv * (float)lh - 0.5f;
+            const float fx0 = floorf(x), fy0 = floorf(y);
+            const float tx = x - fx0, ty = y - fy0;
+            const uint32_t x0 = (uint32_t)(int)fx0 & (lw - 1), x1 = (uint32_t)((int)fx0 + 1) & (lw - 1);
+            const uint32_t y0 = (uint32_t)(int)fy0 & (lh - 1), y1 = (uint32_t)((int)fy0 + 1) & (lh - 1);
+            const uint32_t t00 = sc.texels[off + (size_t)y0 * lw + x0], t01 = sc.texels[off + (size_t)y0 * lw + x1];
+            const uint32_t t10 = sc.texels[off + (size_t)y1 * lw + x0], t11 = sc.texels[off + (size_t)y1 * lw + x1];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const float c00 = (float)((t00 >> (8 * c)) & 0xFFu), c01 = (float)((t01 >> (8 * c)) & 0xFFu);
+                const float c10 = (float)((t10 >> (8 * c)) & 0xFFu), c11 = (float)((t11 >> (8 * c)) & 0xFFu);
+                const float top = fmaf(tx, c01 - c00, c00), bot = fmaf(tx, c11 - c10, c10);
+                out[c] = to_u8(fmaf(ty, bot - top, top));
+            }
+            return;
+        }
         uint32_t x = min((uint32_t)(fu * (float)lw), lw - 1), y = min((uint32_t)(fv * (float)lh), lh - 1);
         uint32_t texel = sc.texels[off + (size_t)y * lw + x];
         out[0] = (uint8_t)(texel & 0xFFu);
@@ -261,13 +279,13 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
             bool found = false;
             if (ok && piece_colour(s0, s1, s2, i, j, d, rgb, uv_area2, area2)) {
                 found = true;
-                piece_output(sc, textured, rgb, uv_area2, area2, out);
+                piece_output(sc, textured, fp.bilinear != 0, rgb, uv_area2, area2, out);
             }
             // the second fan piece; should rounding ever make both cover this pixel, the nearer one is
             // the one the z-test kept (the first one on a tie)
             float d2;
             if (ok && m == 4 && piece_colour(s0, s2, s3, i, j, d2, rgb, uv_area2, area2) && (!found || d2 < d))
-                piece_output(sc, textured, rgb, uv_area2, area2, out);
+                piece_output(sc, textured, fp.bilinear != 0, rgb, uv_area2, area2, out);
         }
     }
     const u64 cm = ballot64(clipped);
@@ -407,7 +425,7 @@ __global__ __launch_bounds__(64) void k_shade_clipped(const SceneDev* __restrict
                     if (piece_colour(s0, s1, s2, i, j, d, rgb, uv_area2, area2) && (!found || d < best)) {
                         found = true;
                         best = d;
-                        piece_output(sc, textured, rgb, uv_area2, area2, out);
+                        piece_output(sc, textured, fp.bilinear != 0, rgb, uv_area2, area2, out);
                     }
                     s1 = s2;
                 }

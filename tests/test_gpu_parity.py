@@ -184,16 +184,19 @@ def test_supersampled_output_is_the_box_filter_of_the_double_resolution_render(r
             r.render(ids, w.view_proj, want_tri_id=True)
 
 
+@pytest.mark.parametrize("bilinear", [False, True])
 @pytest.mark.parametrize("cfg,B,scale,H,W", [(4, 16, 0.02, 64, 64), (1, 32, 1.0, 64, 64), (4, 6, 0.05, 96, 128)])
-def test_textured_scenes_match_oracle_texels(cfg, B, scale, H, W):
+def test_textured_scenes_match_oracle_texels(cfg, B, scale, H, W, bilinear):
     """Texture coordinates interpolated (and clipped) like colours, one mip level per rasterised
-    triangle, nearest texel: the same float sequence as the oracle, so every byte is equal."""
+    triangle, nearest texel or the bilinear blend of four: the same float sequence as the oracle,
+    so every byte is equal."""
     import torch
     import oracle
     import paper_2103_07013_amd as bps
     w = synth.build_config(cfg, B=B, scale=scale)
-    ref = oracle.render_batch(w.scenes, w.scene_ids, w.view_proj, H, W, rgbd=True, textured=True)
-    with bps.Renderer(max_batch=w.B, height=H, width=W, mode=bps.MODE_RGBD) as r:
+    ref = oracle.render_batch(w.scenes, w.scene_ids, w.view_proj, H, W, rgbd=True, textured=True, bilinear=bilinear)
+    with bps.Renderer(max_batch=w.B, height=H, width=W, mode=bps.MODE_RGBD,
+                      flags=bps.FLAG_BILINEAR if bilinear else 0) as r:
         hs = [r.load_scene_textured(s.vertices, s.indices, s.uvs, s.texture) for s in w.scenes]
         ids = np.array([hs[k] for k in w.scene_ids], np.int32)
         depth, rgb, tid = r.render(ids, w.view_proj, want_tri_id=True)
@@ -273,9 +276,11 @@ def test_random_scenes_cameras_and_frame_sizes(seed):
     assert (ref["tri_id"] != NOHIT).mean() > 0.2
 
 
-def test_random_soup_rgbd_and_texture_through_the_clipper():
+@pytest.mark.parametrize("bilinear", [False, True])
+def test_random_soup_rgbd_and_texture_through_the_clipper(bilinear):
     """Colour and texture coordinates of triangles cut by every frustum plane (wide field of view,
-    near plane inside the geometry, rolled cameras): bytes equal the oracle's."""
+    near plane inside the geometry, rolled cameras; texture coordinates far outside [0, 1), so
+    the bilinear blend wraps around the texture's sides all the time): bytes equal the oracle's."""
     import torch
     import oracle
     import paper_2103_07013_amd as bps
@@ -298,8 +303,8 @@ def test_random_soup_rgbd_and_texture_through_the_clipper():
         Ms.append((P @ R @ V).astype(np.float32))
     Ms = np.stack(Ms)
     ref_c = oracle.render_scene(v, idx, Ms, 64, 64, colors=colors)
-    ref_t = oracle.render_scene(v, idx, Ms, 64, 64, uvs=uvs, texture=tex)
-    with bps.Renderer(max_batch=20, mode=bps.MODE_RGBD) as r:
+    ref_t = oracle.render_scene(v, idx, Ms, 64, 64, uvs=uvs, texture=tex, bilinear=bilinear)
+    with bps.Renderer(max_batch=20, mode=bps.MODE_RGBD, flags=bps.FLAG_BILINEAR if bilinear else 0) as r:
         a = r.load_scene(v, idx, colors)
         b = r.load_scene_textured(v, idx, uvs, tex)
         ids = np.array([a] * 10 + [b] * 10, np.int32)

@@ -723,3 +723,82 @@ def test_clipper_capacity_is_never_reached_and_is_reported_if_it_were():
     overflows, largest = oracle.clip_stats()
     assert overflows == 0
     assert 7 <= largest <= 10, largest          # six planes cut: up to nine corners, one more through rounding at most
+
+
+# ---------------------------------------------------------------- bilinear texture filtering (rule N11)
+
+def test_bilinear_constant_texture_texel_centres_and_midpoints():
+    """N11 against what bilinear filtering must give: a constant texture stays constant; at a texel
+    centre the result is that texel; halfway between two texels it is their mean (a tie rounds to
+    even, as the rule's lrint says); a linear ramp is reproduced exactly between texel centres."""
+    rng = np.random.default_rng(5)
+    const = np.full((8, 8, 3), (17, 200, 93), np.uint8)
+    for u, v in rng.uniform(-3, 3, (50, 2)):
+        assert tuple(oracle.sample(const, 0, u, v, bilinear=True)) == (17, 200, 93)
+    tex = rng.integers(0, 256, (8, 16, 3), dtype=np.uint8)           # 16 wide, 8 high
+    for _ in range(60):
+        i, j = int(rng.integers(0, 16)), int(rng.integers(0, 8))
+        got = oracle.sample(tex, 0, (i + 0.5) / 16 + int(rng.integers(-2, 3)), (j + 0.5) / 8, bilinear=True)
+        assert np.array_equal(got, tex[j, i])
+    ramp = np.zeros((4, 8, 3), np.uint8)
+    ramp[:, :, 0] = np.arange(8) * 10                                 # value 10 x at texel x
+    ramp[:, :, 1] = (np.arange(4) * 20)[:, None]
+    for x in (1.0, 1.25, 2.5, 3.75, 6.0):                             # in texel-centre units, away from the wrap
+        got = oracle.sample(ramp, 0, (x + 0.5) / 8, (1.5 + 0.5) / 4, bilinear=True)
+        assert got[0] == int(np.rint(10 * x)) and got[1] == 30        # halfway between rows 1 and 2: (20 + 40) / 2
+    two = np.zeros((1, 2, 3), np.uint8)
+    two[0, 0], two[0, 1] = (10, 0, 0), (11, 0, 0)
+    assert oracle.sample(two, 0, 0.5, 0.5, bilinear=True)[0] == 10    # 10.5 rounds to even
+
+
+def test_bilinear_wraps_at_the_border_and_uses_the_chosen_level():
+    """The texture repeats: left of the first texel centre the last texel of the row is blended in
+    (and above the first row the last one); at a coarser level the same rule applies to that level's
+    texels (the pyramid is N10's)."""
+    ramp = np.zeros((4, 8, 3), np.uint8)
+    ramp[:, :, 0] = np.arange(8) * 10
+    ramp[:, :, 1] = (np.arange(4) * 20)[:, None]
+    assert oracle.sample(ramp, 0, 0.0, 0.125, bilinear=True)[0] == 35         # halfway between texel 7 (70) and texel 0 (0)
+    assert oracle.sample(ramp, 0, 1.0 / 64, 0.125, bilinear=True)[0] == 26    # x = -0.375: 0.375 * 70 = 26.25
+    assert oracle.sample(ramp, 0, 1.0 / 16, 0.0, bilinear=True)[1] == 30      # halfway between row 3 (60) and row 0 (0)
+    # level 1 of the ramp: texels (0+10)/2 ... -> 5, 25, 45, 65 (rounded pyramid), two rows 10 and 50
+    assert [int(oracle.sample(ramp, 1, (i + 0.5) / 4, 0.25, bilinear=True)[0]) for i in range(4)] == [5, 25, 45, 65]
+    assert oracle.sample(ramp, 1, 0.5, 0.25, bilinear=True)[0] == 35          # between 25 and 45
+    assert oracle.sample(ramp, 1, 0.375, 0.5, bilinear=True)[1] == 30         # between rows 10 and 50 of level 1
+    one = np.full((1, 1, 3), 77, np.uint8)
+    assert tuple(oracle.sample(one, 0, 0.3, 0.9, bilinear=True)) == (77, 77, 77)
+
+
+def test_bilinear_render_of_a_camera_facing_textured_quad():
+    """Through the renderer: a camera-facing quad whose texture coordinates put exactly one texel on
+    every pixel, shifted by half a texel, shows the mean of horizontally adjacent texels; with the
+    nearest rule the same picture shows single texels."""
+    H = W = 16
+    z = -2.0
+    v = np.array([[-2, -2, z], [2, -2, z], [2, 2, z], [-2, 2, z]], np.float32)     # fills the 90-degree view exactly
+    idx = np.array([[0, 1, 2], [0, 2, 3]], np.uint32)
+    tex = np.random.default_rng(9).integers(0, 256, (16, 16, 3), dtype=np.uint8)
+    shift = 0.5 / 16
+    uv0 = np.array([[0, 1], [1, 1], [1, 0], [0, 0]], np.float32)      # pixel (i, j) looks at the centre of one texel
+    uv = uv0 + np.array([shift, 0], np.float32)                       # ... and now at the border of texels i and i + 1
+    M = cam()
+    near = oracle.render_scene(v, idx, M[None], H, W, uvs=uv0, texture=tex)
+    lin0 = oracle.render_scene(v, idx, M[None], H, W, uvs=uv0, texture=tex, bilinear=True)
+    lin = oracle.render_scene(v, idx, M[None], H, W, uvs=uv, texture=tex, bilinear=True)
+    assert np.all(near["tri_id"][0] != NOHIT)
+    # which texel row each image row shows (unambiguous: texel centres)
+    rows = [int(np.flatnonzero(np.all(near["rgb"][0, j, 4] == tex[:, 4], axis=1))[0]) for j in range(H)]
+    assert sorted(rows) == list(range(16))
+    for j in range(H):
+        assert np.array_equal(near["rgb"][0, j], tex[rows[j]])
+    # at texel centres filtering changes nothing (up to the rounding of the interpolated coordinates: the
+    # weight of the neighbour is at most a few 1e-6)
+    assert np.array_equal(lin0["rgb"][0], near["rgb"][0])
+    t = tex.astype(np.int32)
+    for j in range(H):
+        for i in range(W - 1):
+            pair = t[rows[j], i] + t[rows[j], i + 1]
+            got = lin["rgb"][0, j, i].astype(np.int32)
+            even = pair % 2 == 0
+            assert np.all(got[even] == pair[even] // 2)                       # the mean of the two texels
+            assert np.all(np.abs(2 * got[~even] - pair[~even]) == 1)          # a tie: either neighbour of the half
