@@ -209,7 +209,7 @@ def rotation_run(bps, torch, w, steps, warmup):
     handles = [r.load_scene(s.vertices, s.indices) for s in w.scenes]
     spare = [synth.make_multiroom_scene(w.scenes[0].T, seed=1500 + k) for k in range(2)]
     pool = list(w.scenes) + spare
-    state = {"ids": np.array([handles[k] for k in w.scene_ids], np.int32), "stop": False, "loaded": 0, "load_s": 0.0}
+    state = {"ids": np.array([handles[k] for k in w.scene_ids], np.int32), "stop": False, "loaded": 0, "load_s": 0.0, "submitted": 0}
     lock = threading.Lock()
     copy_stream = torch.cuda.Stream()
     vp = torch.from_numpy(w.view_proj).cuda()
@@ -229,7 +229,12 @@ def rotation_run(bps, torch, w, steps, warmup):
             slot_handles[k] = new
             with lock:
                 state["ids"] = np.array([slot_handles[j] for j in w.scene_ids], np.int32)
-                bps.bps_unload_scene(r.handle, old)     # requests that still use it are queued: allowed
+                mark = state["submitted"]
+            # the render thread may have read the old ids just before the swap: the old scene is retired once
+            # that request has been submitted (requests that use it may well still be queued: allowed)
+            while state["submitted"] < mark + 2 and not state["stop"]:
+                time.sleep(0.0002)
+            bps.bps_unload_scene(r.handle, old)
             state["loaded"] += 1
             n += 1
 
@@ -240,8 +245,10 @@ def rotation_run(bps, torch, w, steps, warmup):
     th.start()
     t0 = time.perf_counter()
     for _ in range(steps):
-        with lock:      # the loader retires the old handle only after taking this lock: never between snapshot and request
-            bps.bps_render(r.handle, state["ids"], vp, depth, stream=stream)
+        with lock:
+            ids = state["ids"]
+        bps.bps_render(r.handle, ids, vp, depth, stream=stream)
+        state["submitted"] += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     state["stop"] = True
