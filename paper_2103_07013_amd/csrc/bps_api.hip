@@ -356,11 +356,16 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
         r->rh = cfg->height * ss;
         r->tile_w = tile_of(r->rw);
         r->tile_h = tile_of(r->rh);
-        if (const char* e = std::getenv("BPS_TILE")) {   // tuning knob: force a tile size
+#ifdef BPS_TUNING_KNOBS      // experiments only: not compiled into the library that ships
+        if (const char* e = std::getenv("BPS_TILE")) {   // force a tile size
             int v = std::atoi(e);
-            if (v >= 8 && v <= 64) { r->tile_w = std::min(v, r->rw); r->tile_h = std::min(v, r->rh); }   // a window is at most 64x64 pixels
+            if (v >= 8 && v <= 64) { r->tile_w = std::min(v, r->rw); r->tile_h = std::min(v, r->rh); }
         }
+#endif
         r->tiles = ((r->rw + r->tile_w - 1) / r->tile_w) * ((r->rh + r->tile_h - 1) / r->tile_h);
+        // the raster kernel's depth tiles and footprint records are laid out for windows of at most 64x64 pixels
+        if (r->tile_w > 64 || r->tile_h > 64 || ((r->tile_w + 7) / 8) * ((r->tile_h + 7) / 8) > bps::kHizTiles)
+            return fail(r, BPS_ERR_UNSUPPORTED, "bps_create: window %dx%d exceeds what the raster kernel is laid out for", r->tile_w, r->tile_h);
         // preferred work-group size whose LDS footprint leaves room for a useful survivor list
         const int order[4] = {512, 384, 256, 1024};
         r->threads = 0;
@@ -384,8 +389,10 @@ bps_status bps_create(const bps_config* cfg, bps_renderer** out) {
                         r->max_lds);
         r->list_cap = fit_cap(r->threads);
         r->round_target = r->list_cap;
-        if (const char* e = std::getenv("BPS_ROUND_TARGET")) r->round_target = std::max(1, std::atoi(e));   // tuning knob
-        if (const char* e = std::getenv("BPS_FIRST_ROUND")) r->first_round = std::max(1, std::atoi(e));     // tuning knob
+#ifdef BPS_TUNING_KNOBS
+        if (const char* e = std::getenv("BPS_ROUND_TARGET")) r->round_target = std::max(1, std::atoi(e));
+        if (const char* e = std::getenv("BPS_FIRST_ROUND")) r->first_round = std::max(1, std::atoi(e));
+#endif
         r->lds = bps::lds_bytes(r->tile_h, r->tile_w, r->threads, r->list_cap);
         BPS_HIP(r, bps::prepare_raster(r->threads, r->lds));
         BPS_HIP(r, hipMalloc((void**)&r->d_scenes, sizeof(bps::SceneDev) * kMaxScenes));
