@@ -875,6 +875,21 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         // the others: the flush (one pass of the clipper, mostly waiting for memory) then overlaps the
         // clusters the slower wavefronts are still drawing.
         if (last_round) break;
+        // What the wavefront has queued goes into the depth buffer now, so that the depth tiles and the
+        // next round's tests see everything this round drew.  Triangles waiting for the clipper are the
+        // ones along the window's border: until they are drawn, no footprint that touches a border
+        // pixel can be found hidden.
+        if (occlusion && clip_count > 0) {
+            wave_lds_sync();
+            drain_clip(L, 0, clip_count, small_count, sc, M, fq, win, lane, vis);
+            clip_count = 0;
+        }
+        if (occlusion && small_count > 0) {
+            wave_lds_sync();
+            drain_small(L, small_count, lane, vis, win, g_ctri_id);
+            wave_lds_sync();
+            small_count = 0;
+        }
         __syncthreads();
         if (tid == 0) { *list_count = 0u; *pop_count = 0u; *reserved = 0u; }
         if (occlusion) {   // (more blocks are waiting, or the loop would have ended above)
