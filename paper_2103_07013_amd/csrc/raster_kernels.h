@@ -66,20 +66,29 @@ constexpr int kSmallMax = 9;           // pixel centres a "small" triangle may t
 constexpr uint32_t kInvalid = 0x40u;   // outcode bit: vertex unusable, drop its triangles
 constexpr uint32_t kNoProject = 0x80u; // outcode bit: vertex has no finite screen position (w <= 0 or overflow)
 
-// per-wave LDS block: 64 staged vertices (8 B + 4 B outcode each), small queue 8 x 64 words,
-// clip queue 192 words
-constexpr uint32_t kListCap64 = 1408;   // survivor-list capacity of the 64x64 instance (two groups per compute unit)
-constexpr uint32_t kWaveLdsBytes = 64 * 12 + 8 * 64 * 4 + 192 * 4;
+// per-wave LDS block: 64 staged vertices (8 B + 4 B outcode each), small queue 8 x 64 words
+constexpr uint32_t kListCap64 = 1216;   // survivor-list capacity of the 64x64 instance (two groups per compute unit)
+constexpr uint32_t kWaveLdsBytes = 64 * 12 + 8 * 64 * 4;
+
+// The work-group's ring of triangles waiting for the clipper.  A wavefront adds at most 128 entries
+// between two looks at the ring and then drains it below 64, and at most 64 entries per wavefront are
+// claimed but not yet read: never more than 64 + 192 per wavefront in use, so 256 per wavefront
+// (rounded up to a power of two) cannot wrap onto a live entry.
+__host__ __device__ constexpr uint32_t clip_ring_entries(int threads) {
+    uint32_t need = 256u * (uint32_t)(threads / 64), n = 256u;
+    while (n < need) n *= 2u;
+    return n;
+}
 
 constexpr int kOrderCap = 1024;        // blocks of one item that can be depth-sorted
 constexpr int kHizTiles = 64;          // 8x8-pixel tiles of a window of at most 64x64 pixels
 constexpr int kDepthBins = 128;        // bins of the per-round depth sort of surviving clusters
 
 // visibility buffer, per-wave blocks, survivor list (8 B record + two 2 B sort words per cluster),
-// block order, depth histogram and its prefix, four counters
+// block order, depth histogram and its prefix, eight counters, clip ring
 __host__ __device__ inline size_t lds_bytes(int tile_h, int tile_w, int threads, int list_cap) {
     return (size_t)tile_h * tile_w * 8 + (size_t)(threads / 64) * kWaveLdsBytes + (size_t)list_cap * 12 + kOrderCap * 2 +
-           2 * kDepthBins * 4 + kHizTiles * 4 + 32;
+           2 * kDepthBins * 4 + kHizTiles * 4 + 32 + (size_t)clip_ring_entries(threads) * 4;
 }
 
 // DIAG = true is the instance launched while diagnostics are on; it alone keeps counters and timers.

@@ -19,7 +19,6 @@ struct WaveLds {
     float2* stage;      // [64] staged vertices of the current cluster: (packed xy bits, 1/w)
     uint32_t* stage_oc; // [64] their outcodes
     uint32_t* smallq;   // [8][64] struct-of-arrays: xy0 xy1 xy2 iw0 iw1 iw2 id box
-    uint32_t* clipq;    // [192] cluster << 7 | slot
     uint32_t* tally;    // diagnostics (wave-private registers, dead code in the production instances): see kT*
 };
 // diagnostics tallies
@@ -319,11 +318,11 @@ __device__ __forceinline__ int depth_bin(u64 e) {
 }
 
 // One lane per queued straddling triangle: clip, project, fan, hand the pieces to emit().
-__device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, int& small_count, const SceneDev& sc,
+__device__ __forceinline__ void drain_clip(const WaveLds& L, uint32_t ref, int n, int& small_count, const SceneDev& sc,
                                            const float (&M)[16], const FrameParams& fp, const Window& win, int lane,
                                            u64* vis) {
     bool have = lane < n;
-    uint32_t ref = have ? L.clipq[first + lane] : 0u;
+    if (!have) ref = 0u;
     uint32_t c = ref >> 7, slot = ref & 127u;
     uint32_t t = gptr(sc.ctris)[(size_t)c * 128 + slot] & 0x00FFFFFFu;
     const BPS_GLOBAL float* cv = gptr(sc.cverts) + (size_t)c * 192;
@@ -457,12 +456,61 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, int first, int n, i
     }
 }
 
-// Append straddling triangles to the wave's clip queue (drained by the caller once per cluster,
-// so at most 63 + 128 entries are ever pending).
-__device__ __forceinline__ void push_clip(const WaveLds& L, int& count, bool want, uint32_t ref, u64 mask) {
+// The clip ring is shared by the work-group: with one ring a clipper pass of 64 triangles comes up
+// eight times sooner than with a queue per wavefront, and what waits for the clipper are the triangles
+// along the window's border, without which no footprint touching a border pixel can be found hidden.
+//   tail  entries reserved by producers (one LDS atomic per wavefront and push)
+//   head  entries claimed by consumers
+// An entry is written right after its reservation and reads kClipEmpty until then; the consumer of a
+// claimed entry waits for it to turn up and puts kClipEmpty back.
+constexpr uint32_t kClipEmpty = 0xFFFFFFFFu;      // no entry: cluster << 7 | slot stays below 2^30
+struct ClipRing {
+    uint32_t* slot;      // [mask + 1]
+    uint32_t* tail;
+    uint32_t* head;
+    uint32_t mask;
+};
+
+// tail_seen: the ring's tail right after this wavefront's reservation
+__device__ __forceinline__ void push_clip(const ClipRing& R, bool want, uint32_t ref, u64 mask, int lane, uint32_t& tail_seen) {
     if (mask == 0) return;
-    if (want) L.clipq[count + (int)rank_below(mask)] = ref;
-    count += __popcll(mask);
+    const uint32_t count = (uint32_t)__popcll(mask);
+    uint32_t pos = 0;
+    if (lane == 0) pos = atomicAdd(R.tail, count);
+    pos = __builtin_amdgcn_readfirstlane(pos);
+    if (want) R.slot[(pos + rank_below(mask)) & R.mask] = ref;
+    tail_seen = pos + count;
+}
+
+// Claims up to 64 entries if at least `at_least` are waiting; returns how many (0: none) and hands
+// lane k < n its entry.  head_seen, tail_seen: the ring's head and tail as last seen by this wavefront
+// (the true head is never behind head_seen).
+__device__ __forceinline__ int pop_clip(const ClipRing& R, uint32_t at_least, int lane, uint32_t& ref, uint32_t& head_seen,
+                                        uint32_t& tail_seen) {
+    uint32_t start = 0, n = 0, h = 0, t = 0;
+    if (lane == 0) {
+        h = __hip_atomic_load(R.head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (;;) {
+            t = __hip_atomic_load(R.tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const uint32_t waiting = t - h;
+            if (waiting < at_least || waiting == 0u) break;
+            const uint32_t take = min(waiting, 64u);
+            const uint32_t seen = atomicCAS(R.head, h, h + take);
+            if (seen == h) { start = h; n = take; h += take; break; }
+            h = seen;
+        }
+    }
+    start = __builtin_amdgcn_readfirstlane(start);
+    n = __builtin_amdgcn_readfirstlane(n);
+    head_seen = __builtin_amdgcn_readfirstlane(h);
+    tail_seen = __builtin_amdgcn_readfirstlane(t);
+    ref = 0u;
+    if ((uint32_t)lane < n) {
+        uint32_t* s = &R.slot[(start + (uint32_t)lane) & R.mask];
+        do ref = __hip_atomic_load(s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); while (ref == kClipEmpty);
+        __hip_atomic_store(s, kClipEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    return (int)n;
 }
 
 }  // namespace
@@ -502,7 +550,6 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     L.stage = reinterpret_cast<float2*>(wbase);
     L.stage_oc = reinterpret_cast<uint32_t*>(wbase + 64 * 8);
     L.smallq = reinterpret_cast<uint32_t*>(wbase + 64 * 12);
-    L.clipq = reinterpret_cast<uint32_t*>(wbase + 64 * 12 + 8 * 64 * 4);
 
     unsigned char* shared = smem + (size_t)HW * 8 + (size_t)NW * kWaveLdsBytes;
     u64* list = reinterpret_cast<u64*>(shared);                                 // [list_cap] surviving clusters
@@ -517,6 +564,11 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     uint32_t* next_block = counters + 2;   // blocks handed out so far (whole item)
     uint32_t* reserved = counters + 3;     // upper bound on list_count once every tester has appended
     uint32_t* blocks_in_view = counters + 4;   // blocks of the item that are not wholly outside the frustum
+    ClipRing ring;
+    ring.tail = counters + 5;
+    ring.head = counters + 6;
+    ring.slot = counters + 8;
+    ring.mask = clip_ring_entries(NT) - 1u;
 
     const WorkItem item = items[blockIdx.x];     // the host or the planner has put the items in launch order
     const SceneDev sc = scenes[item.scene];
@@ -550,7 +602,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     const int npix = win.w * win.h;
     for (int p = tid; p < npix; p += NT) vis[p] = kEmptyKey;
 
-    int small_count = 0, clip_count = 0;
+    int small_count = 0;
+    uint32_t clip_tail_seen = 0u, clip_head_seen = 0u;    // this wavefront's last view of the clip ring
     // diagnostics (only when the host passes a counter block): per-wave tallies, one atomic each at the end
     uint32_t st_tested = 0, st_boxed = 0, st_drawn = 0, st_straddle = 0, st_hidden = 0, st_hiz = 0;
     const unsigned long long t_start = stats ? wall_clock64() : 0ull;
@@ -575,6 +628,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     // ---- prologue: counters, and the item's blocks ordered near to far
     if (tid < 8) counters[tid] = 0u;
     for (int t = tid; t < kHizTiles; t += NT) hiz[t] = 0xFFFFFFFFu;   // nothing drawn yet: no tile hides anything
+    for (uint32_t t = tid; t <= ring.mask; t += NT) ring.slot[t] = kClipEmpty;
     __syncthreads();
     const bool sorted = CULL != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)list_cap && nb_item > 1;
     if (sorted) {
@@ -857,17 +911,22 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                     const bool straddle = live && crossing && (has || behind);
                     const u64 straddle_mask = live_mask & crossing_mask & (has_mask | ballot64(behind));
                     st_straddle += (uint32_t)__popcll(straddle_mask);
-                    push_clip(L, clip_count, straddle, (c << 7) | (uint32_t)(slot * 64 + lane), straddle_mask);
+                    push_clip(ring, straddle, (c << 7) | (uint32_t)(slot * 64 + lane), straddle_mask, lane, clip_tail_seen);
                 }
                 emit(L, small_count, fast && has, lo, ext, __float_as_uint(a.x), __float_as_uint(b.x),
                      __float_as_uint(d.x), a.y, b.y, d.y, c * 128u + (uint32_t)(slot * 64 + lane), g_ctri_id, lane, vis,
                      win, fast_mask & has_mask);
             }
-            // ---- clip queue: full wavefronts only while streaming
-            while (clip_count >= 64) {
+            // ---- clip ring: full wavefronts only while streaming.  The ring is looked at only when this
+            // wavefront's own view says 64 may be waiting: its view of the tail dates from its last push, its
+            // view of the head is never ahead of the head, so every push that leaves 64 or more waiting is
+            // followed by a look.
+            while (clip_tail_seen - clip_head_seen >= 64u) {
+                uint32_t ref;
+                const int n = pop_clip(ring, 64u, lane, ref, clip_head_seen, clip_tail_seen);
+                if (n == 0) break;
                 wave_lds_sync();
-                drain_clip(L, clip_count - 64, 64, small_count, sc, M, fq, win, lane, vis);
-                clip_count -= 64;
+                drain_clip(L, ref, n, small_count, sc, M, fq, win, lane, vis);
             }
         }
         TICK(5);
@@ -879,10 +938,14 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         // next round's tests see everything this round drew.  Triangles waiting for the clipper are the
         // ones along the window's border: until they are drawn, no footprint that touches a border
         // pixel can be found hidden.
-        if (occlusion && clip_count > 0) {
-            wave_lds_sync();
-            drain_clip(L, 0, clip_count, small_count, sc, M, fq, win, lane, vis);
-            clip_count = 0;
+        if (occlusion) {
+            for (;;) {
+                uint32_t ref;
+                const int n = pop_clip(ring, 1u, lane, ref, clip_head_seen, clip_tail_seen);
+                if (n == 0) break;
+                wave_lds_sync();
+                drain_clip(L, ref, n, small_count, sc, M, fq, win, lane, vis);
+            }
         }
         if (occlusion && small_count > 0) {
             wave_lds_sync();
@@ -941,9 +1004,13 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         __syncthreads();
         TICK(6);
     }
-    if (clip_count > 0) {
+    // whatever a wavefront that is still drawing adds later, that wavefront takes when it gets here
+    for (;;) {
+        uint32_t ref;
+        const int n = pop_clip(ring, 1u, lane, ref, clip_head_seen, clip_tail_seen);
+        if (n == 0) break;
         wave_lds_sync();
-        drain_clip(L, 0, clip_count, small_count, sc, M, fq, win, lane, vis);
+        drain_clip(L, ref, n, small_count, sc, M, fq, win, lane, vis);
     }
     if (small_count > 0) {
         wave_lds_sync();
