@@ -9,10 +9,10 @@
 //   vertex phase   one lane per vertex: clip = M v, six-plane outcodes, projection, 1/256-px snap
 //   cluster cull   all 64 vertices outside one plane (wave ballot)  -> next cluster
 //   triangle phase two triangles per lane: outcode reject, bounding box vs pixel centres
-//   compaction     survivors are appended to per-wave LDS queues with ballot + prefix count so
+//   compaction     survivors are appended to LDS queues with ballot + prefix count so
 //                  that the expensive steps run on full wavefronts:
-//                    small queue  triangles touching <= 4 pixel centres, one lane per triangle
-//                    clip queue   triangles straddling a frustum plane, one lane per triangle
+//                    small queue  (per wavefront) triangles touching <= 9 pixel centres, one lane per triangle
+//                    clip ring    (per work-group) triangles straddling a frustum plane, one lane per triangle
 //                  large triangles are rasterised by the whole wavefront, 8x8 pixels at a time.
 // All float arithmetic follows one fixed IEEE sequence (explicit fmaf, no contraction, exact
 // division) so that coverage and ids are reproducible bit for bit.
