@@ -317,11 +317,74 @@ __device__ __forceinline__ int depth_bin(u64 e) {
     return min(max(k, 0), kDepthBins - 1);
 }
 
+// The clip ring is shared by the work-group: with one ring a clipper pass of 64 triangles comes up
+// eight times sooner than with a queue per wavefront, and what waits for the clipper are the triangles
+// along the window's border, without which no footprint touching a border pixel can be found hidden.
+//   tail  entries reserved by producers (one LDS atomic per wavefront and push)
+//   head  entries claimed by consumers
+// An entry is written right after its reservation and reads kClipEmpty until then; the consumer of a
+// claimed entry waits for it to turn up and puts kClipEmpty back.
+constexpr uint32_t kClipEmpty = 0xFFFFFFFFu;      // no entry: cluster << 7 | slot stays below 2^30
+struct ClipRing {
+    uint32_t* slot;      // [mask + 1]
+    uint32_t* tail;
+    uint32_t* head;
+    uint32_t mask;
+};
+
+// tail_seen: the ring's tail right after this wavefront's reservation
+__device__ __forceinline__ void push_clip(const ClipRing& R, bool want, uint32_t ref, u64 mask, int lane, uint32_t& tail_seen) {
+    if (mask == 0) return;
+    const uint32_t count = (uint32_t)__popcll(mask);
+    uint32_t pos = 0;
+    if (lane == 0) pos = atomicAdd(R.tail, count);
+    pos = __builtin_amdgcn_readfirstlane(pos);
+    if (want) R.slot[(pos + rank_below(mask)) & R.mask] = ref;
+    tail_seen = pos + count;
+}
+
+// Claims up to 64 entries if at least `at_least` are waiting; returns how many (0: none) and hands
+// lane k < n its entry.  head_seen, tail_seen: the ring's head and tail as last seen by this wavefront
+// (the true head is never behind head_seen).
+__device__ __forceinline__ int pop_clip(const ClipRing& R, uint32_t at_least, int lane, uint32_t& ref, uint32_t& head_seen,
+                                        uint32_t& tail_seen) {
+    uint32_t start = 0, n = 0, h = 0, t = 0;
+    if (lane == 0) {
+        h = __hip_atomic_load(R.head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (;;) {
+            t = __hip_atomic_load(R.tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const uint32_t waiting = t - h;
+            if (waiting < at_least || waiting == 0u) break;
+            const uint32_t take = min(waiting, 64u);
+            const uint32_t seen = atomicCAS(R.head, h, h + take);
+            if (seen == h) { start = h; n = take; h += take; break; }
+            h = seen;
+        }
+    }
+    start = __builtin_amdgcn_readfirstlane(start);
+    n = __builtin_amdgcn_readfirstlane(n);
+    head_seen = __builtin_amdgcn_readfirstlane(h);
+    tail_seen = __builtin_amdgcn_readfirstlane(t);
+    ref = kClipEmpty;
+    if ((uint32_t)lane < n) {
+        // The producer writes the entry right after reserving it and waits for nothing in between, so the
+        // wait is a few cycles at most; it is bounded all the same, so that every wavefront leaves the
+        // kernel whatever happens (a lane whose entry never turned up draws nothing).
+        uint32_t* s = &R.slot[(start + (uint32_t)lane) & R.mask];
+        for (int spin = 0; spin < (1 << 22); ++spin) {
+            ref = __hip_atomic_load(s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (ref != kClipEmpty) break;
+        }
+        __hip_atomic_store(s, kClipEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    return (int)n;
+}
+
 // One lane per queued straddling triangle: clip, project, fan, hand the pieces to emit().
 __device__ __forceinline__ void drain_clip(const WaveLds& L, uint32_t ref, int n, int& small_count, const SceneDev& sc,
                                            const float (&M)[16], const FrameParams& fp, const Window& win, int lane,
                                            u64* vis) {
-    bool have = lane < n;
+    bool have = lane < n && ref != kClipEmpty;
     if (!have) ref = 0u;
     uint32_t c = ref >> 7, slot = ref & 127u;
     uint32_t t = gptr(sc.ctris)[(size_t)c * 128 + slot] & 0x00FFFFFFu;
@@ -454,63 +517,6 @@ __device__ __forceinline__ void drain_clip(const WaveLds& L, uint32_t ref, int n
         b = d;
         wb = wd;
     }
-}
-
-// The clip ring is shared by the work-group: with one ring a clipper pass of 64 triangles comes up
-// eight times sooner than with a queue per wavefront, and what waits for the clipper are the triangles
-// along the window's border, without which no footprint touching a border pixel can be found hidden.
-//   tail  entries reserved by producers (one LDS atomic per wavefront and push)
-//   head  entries claimed by consumers
-// An entry is written right after its reservation and reads kClipEmpty until then; the consumer of a
-// claimed entry waits for it to turn up and puts kClipEmpty back.
-constexpr uint32_t kClipEmpty = 0xFFFFFFFFu;      // no entry: cluster << 7 | slot stays below 2^30
-struct ClipRing {
-    uint32_t* slot;      // [mask + 1]
-    uint32_t* tail;
-    uint32_t* head;
-    uint32_t mask;
-};
-
-// tail_seen: the ring's tail right after this wavefront's reservation
-__device__ __forceinline__ void push_clip(const ClipRing& R, bool want, uint32_t ref, u64 mask, int lane, uint32_t& tail_seen) {
-    if (mask == 0) return;
-    const uint32_t count = (uint32_t)__popcll(mask);
-    uint32_t pos = 0;
-    if (lane == 0) pos = atomicAdd(R.tail, count);
-    pos = __builtin_amdgcn_readfirstlane(pos);
-    if (want) R.slot[(pos + rank_below(mask)) & R.mask] = ref;
-    tail_seen = pos + count;
-}
-
-// Claims up to 64 entries if at least `at_least` are waiting; returns how many (0: none) and hands
-// lane k < n its entry.  head_seen, tail_seen: the ring's head and tail as last seen by this wavefront
-// (the true head is never behind head_seen).
-__device__ __forceinline__ int pop_clip(const ClipRing& R, uint32_t at_least, int lane, uint32_t& ref, uint32_t& head_seen,
-                                        uint32_t& tail_seen) {
-    uint32_t start = 0, n = 0, h = 0, t = 0;
-    if (lane == 0) {
-        h = __hip_atomic_load(R.head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        for (;;) {
-            t = __hip_atomic_load(R.tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            const uint32_t waiting = t - h;
-            if (waiting < at_least || waiting == 0u) break;
-            const uint32_t take = min(waiting, 64u);
-            const uint32_t seen = atomicCAS(R.head, h, h + take);
-            if (seen == h) { start = h; n = take; h += take; break; }
-            h = seen;
-        }
-    }
-    start = __builtin_amdgcn_readfirstlane(start);
-    n = __builtin_amdgcn_readfirstlane(n);
-    head_seen = __builtin_amdgcn_readfirstlane(h);
-    tail_seen = __builtin_amdgcn_readfirstlane(t);
-    ref = 0u;
-    if ((uint32_t)lane < n) {
-        uint32_t* s = &R.slot[(start + (uint32_t)lane) & R.mask];
-        do ref = __hip_atomic_load(s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); while (ref == kClipEmpty);
-        __hip_atomic_store(s, kClipEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    }
-    return (int)n;
 }
 
 }  // namespace
