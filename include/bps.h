@@ -165,8 +165,8 @@ bps_status bps_render(bps_renderer *r, const bps_scene *scene_ids, const float *
 
 /* bps_render for callers that cannot allocate: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  It calls no hipMalloc / hipFree / hipHostMalloc and copies nothing
- * from host memory: the work items travel as kernel arguments, and the launch plan (work items, cost
- * and order words) lives in a file-scope __device__ array of the library, 640 KiB on every GPU the
+ * from host memory: the work items travel as kernel arguments, and the launch plan (work items, work
+ * items in launch order, cost words) lives in a file-scope __device__ array of the library, 576 KiB on every GPU the
  * library runs on, held until the process ends.  Same frames as bps_render, bit for bit.
  * Limits: depth renderers without supersampling, forced splits or diagnostics; view_proj must be
  * DEVICE memory; B x (64x64-pixel tiles per frame) <= 16384 work-groups (e.g. 16384 environments at

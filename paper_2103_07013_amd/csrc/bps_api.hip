@@ -27,9 +27,9 @@ constexpr size_t kMaxProfiled = 4096;   // profiled requests remembered between 
 thread_local std::string g_create_error = "";
 
 // ---- scratch of bps_render_static, the entry point that allocates nothing ------------------------
-// Work items as staged, work items in launch order, and one cost and one order word per item.
+// Work items as staged, work items in launch order, and one cost word per item.
 constexpr uint32_t kStaticMaxItems = bps::kMaxPlannedItems;
-constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxItems * (2 * sizeof(bps::WorkItem) + 2 * sizeof(uint32_t));
+constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxItems * (2 * sizeof(bps::WorkItem) + sizeof(uint32_t));
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 // In host code the array's name is only a stand-in: its address on each device is looked up once
 // (bps_create, with that device current) and used from then on.
@@ -847,7 +847,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     // costliest-first dispatch pays off once the launch no longer fits on the device in one go
     const bool planned = fp_cull_enabled(r) && n_items > (size_t)2 * r->num_cu && n_items <= bps::kMaxPlannedItems &&
                          !(r->cfg.flags & BPS_FLAG_NO_DISPATCH_ORDER);
-    const size_t plan_bytes = planned ? n_items * (sizeof(bps::WorkItem) + 2 * sizeof(uint32_t)) + 16 : 0;
+    const size_t plan_bytes = planned ? n_items * (sizeof(bps::WorkItem) + sizeof(uint32_t)) + 16 : 0;
     const size_t need = items_bytes + ids_bytes + vp_bytes + plan_bytes;
     RingSlot& slot = r->ring[r->ring_next];
     r->ring_next = (r->ring_next + 1) % kRing;
@@ -903,7 +903,6 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
     const size_t plan_at = (items_bytes + ids_bytes + vp_bytes + 15) & ~(size_t)15;
     bps::WorkItem* d_ordered = reinterpret_cast<bps::WorkItem*>(payload + plan_at);
     uint32_t* d_cost = reinterpret_cast<uint32_t*>(d_ordered + n_items);
-    uint32_t* d_dispatch = d_cost + n_items;
 
     // ---- RGB-D: the colour pass needs the winning triangle ids even when the caller does not
     if (rgbd && !out_tri_id) {
@@ -946,7 +945,7 @@ bps_status bps_render(bps_renderer* r, const bps_scene* scene_ids, const float* 
         d_stats = r->d_stats;
     }
     if (planned) {
-        bps::launch_plan(pstream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
+        bps::launch_plan(pstream, r->d_scenes, d_items, d_vp, fp, (uint32_t)n_items, d_cost, d_ordered);
         BPS_HIP(r, hipGetLastError());
         if (early) {
             BPS_HIP(r, hipEventRecord(slot.planned, pstream));
@@ -1051,11 +1050,10 @@ bps_status bps_render_static(bps_renderer* r, const bps_scene* scene_ids, const 
         BPS_HIP(r, hipEventSynchronize(slot.done));
         slot.pending = false;
     }
-    // layout of the static array: items as planned, items in launch order, cost words, order words
+    // layout of the static array: items as planned, items in launch order, cost words
     bps::WorkItem* d_items = reinterpret_cast<bps::WorkItem*>(r->static_scratch);
     bps::WorkItem* d_ordered = d_items + kStaticMaxItems;
     uint32_t* d_cost = reinterpret_cast<uint32_t*>(d_ordered + kStaticMaxItems);
-    uint32_t* d_dispatch = d_cost + kStaticMaxItems;
     {   // the items reach the device as kernel arguments, unless the array still holds this very plan
         std::lock_guard<std::mutex> g(g_scratch_mu);
         if (g_scratch_owner[r->device] != r || g_scratch_plan[r->device] != r->plan_version) {
@@ -1076,7 +1074,7 @@ bps_status bps_render_static(bps_renderer* r, const bps_scene* scene_ids, const 
     const bps::FrameParams fp = frame_params(r, 1);
     const bool planned = fp_cull_enabled(r) && n_items > (size_t)2 * r->num_cu && !(r->cfg.flags & BPS_FLAG_NO_DISPATCH_ORDER);
     if (planned) {
-        bps::launch_plan(stream, r->d_scenes, d_items, view_proj, fp, (uint32_t)n_items, d_cost, d_dispatch, d_ordered);
+        bps::launch_plan(stream, r->d_scenes, d_items, view_proj, fp, (uint32_t)n_items, d_cost, d_ordered);
         BPS_HIP(r, hipGetLastError());
     }
     bps::launch_raster(r->threads, dim3((unsigned)n_items), r->lds, stream, r->d_scenes, planned ? d_ordered : d_items, view_proj,

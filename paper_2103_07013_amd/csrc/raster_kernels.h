@@ -109,11 +109,11 @@ __global__ void k_zero_words(unsigned long long* __restrict__ p, size_t n);
 void launch_raster(int threads, dim3 grid, size_t lds, hipStream_t stream, const SceneDev* scenes, const WorkItem* items,
                    const float* view_proj, const FrameParams& fp, unsigned long long* gvis, float* out_depth,
                    uint32_t* out_id, unsigned long long* stats);
-// Fills ordered[n_items] with the items in launch order, costliest first; cost and dispatch are
-// scratch, one word per item each.
+// Fills ordered[n_items] with the items in launch order, costliest first; cost is scratch, one word
+// per item.
 constexpr uint32_t kMaxPlannedItems = 16384;
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
-                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch, WorkItem* ordered);
+                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, WorkItem* ordered);
 hipError_t prepare_raster(int threads, size_t lds);
 // Work items handed over as kernel arguments (no host-to-device copy, no staging memory): up to
 // kPackedItemsPerLaunch items per launch, each packed as env | scene << 16 | tile << 28 (one

@@ -1129,27 +1129,43 @@ __global__ __launch_bounds__(64) void k_item_cost(const SceneDev* __restrict__ s
 // buckets): consecutive work-group indices go to consecutive dies, so every die receives an even
 // sample of the cost distribution, costliest first.
 __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restrict__ cost, uint32_t n_items,
-                                                         uint32_t* __restrict__ dispatch, const WorkItem* __restrict__ items,
-                                                         WorkItem* __restrict__ ordered) {
+                                                         const WorkItem* __restrict__ items, WorkItem* __restrict__ ordered) {
     constexpr uint32_t kBuckets = 2048;
+    constexpr int kPerThread = (int)(kMaxPlannedItems / 1024u);      // every thread keeps its items' costs in registers
     __shared__ uint32_t bucket[kBuckets];
     __shared__ uint32_t scan[1024];
+    static_assert(kMaxPlannedItems <= 65536u, "item indices are kept as 16-bit words");
+    __shared__ uint16_t order_lds[kMaxPlannedItems];                  // the order, before the die-affinity pass
     __shared__ uint32_t largest;
     const uint32_t tid = threadIdx.x;
+    uint32_t my_cost[kPerThread];
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const uint32_t i = tid + (uint32_t)k * 1024u;
+        my_cost[k] = i < n_items ? cost[i] : 0u;
+    }
     for (uint32_t b = tid; b < kBuckets; b += 1024u) bucket[b] = 0u;
     if (tid == 0) largest = 0u;
     __syncthreads();
     {
         uint32_t mx = 0;
-        for (uint32_t i = tid; i < n_items; i += 1024u) mx = max(mx, cost[i]);
-        atomicMax(&largest, mx);
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) mx = max(mx, my_cost[k]);
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, sh, 64));
+        if ((tid & 63u) == 0u) atomicMax(&largest, mx);
     }
     __syncthreads();
     const float scale = largest ? (float)(kBuckets - 1) / (float)largest : 0.0f;
-    auto bucket_of = [&](uint32_t i) -> uint32_t {      // bucket 0 holds the costliest items
-        return kBuckets - 1u - min((uint32_t)((float)cost[i] * scale), kBuckets - 1u);
+    auto bucket_of = [&](uint32_t c) -> uint32_t {      // bucket 0 holds the costliest items
+        return kBuckets - 1u - min((uint32_t)((float)c * scale), kBuckets - 1u);
     };
-    for (uint32_t i = tid; i < n_items; i += 1024u) atomicAdd(&bucket[bucket_of(i)], 1u);
+    uint32_t my_slot[kPerThread];      // position inside the bucket
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const uint32_t i = tid + (uint32_t)k * 1024u;
+        my_slot[k] = i < n_items ? atomicAdd(&bucket[bucket_of(my_cost[k])], 1u) : 0u;
+    }
     __syncthreads();
     // exclusive prefix sum over the buckets: two per thread, then a scan over the 1024 pair sums
     const uint32_t a0 = bucket[2 * tid], a1 = bucket[2 * tid + 1];
@@ -1166,11 +1182,15 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
     uint32_t offset = 0;
     for (uint32_t wv = 0; wv < (tid >> 6); ++wv) offset += scan[wv];
     const uint32_t before = offset + incl - (a0 + a1);
-    __syncthreads();       // scan[] is reused below
+    __syncthreads();       // scan[] is reused below, bucket[] is overwritten now
     bucket[2 * tid] = before;
     bucket[2 * tid + 1] = before + a0;
     __syncthreads();
-    for (uint32_t i = tid; i < n_items; i += 1024u) dispatch[atomicAdd(&bucket[bucket_of(i)], 1u)] = i;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const uint32_t i = tid + (uint32_t)k * 1024u;
+        if (i < n_items) order_lds[bucket[bucket_of(my_cost[k])] + my_slot[k]] = (uint16_t)i;
+    }
     __syncthreads();
     // Die affinity.  Position p of the order runs on die p % 8, and the host lays the items out so
     // that item i's scene is mostly used by items with the same i % 8.  Within every run of 64
@@ -1180,7 +1200,7 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
     uint32_t* slot_item = scan;                       // [16 waves][64]: the window being rebuilt
     const uint32_t lane = tid & 63u, wave = tid >> 6;
     for (uint32_t base = wave * 64u; base + 64u <= n_items; base += 1024u) {
-        const uint32_t item = dispatch[base + lane];
+        const uint32_t item = (uint32_t)order_lds[base + lane];
         const uint32_t home = item & 7u;
         uint32_t* mine = slot_item + wave * 64u;
         mine[lane] = 0xFFFFFFFFu;
@@ -1214,13 +1234,13 @@ __global__ __launch_bounds__(1024) void k_dispatch_order(const uint32_t* __restr
         // than going through the order
         ordered[base + lane] = items[mine[lane]];
     }
-    for (uint32_t i = (n_items & ~63u) + tid; i < n_items; i += 1024u) ordered[i] = items[dispatch[i]];
+    for (uint32_t i = (n_items & ~63u) + tid; i < n_items; i += 1024u) ordered[i] = items[order_lds[i]];
 }
 
 void launch_plan(hipStream_t stream, const SceneDev* scenes, const WorkItem* items, const float* view_proj,
-                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, uint32_t* dispatch, WorkItem* ordered) {
+                 const FrameParams& fp, uint32_t n_items, uint32_t* cost, WorkItem* ordered) {
     hipLaunchKernelGGL(k_item_cost, dim3(n_items), dim3(64), 0, stream, scenes, items, view_proj, fp, n_items, cost);
-    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), 0, stream, cost, n_items, dispatch, items, ordered);
+    hipLaunchKernelGGL(k_dispatch_order, dim3(1), dim3(1024), 0, stream, cost, n_items, items, ordered);
 }
 
 __global__ __launch_bounds__(64) void k_unpack_items(PackedItems packed, uint32_t first, uint32_t count,
