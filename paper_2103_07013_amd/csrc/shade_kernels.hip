@@ -193,7 +193,15 @@ __global__ __launch_bounds__(256) void k_shade(const SceneDev* __restrict__ scen
     __shared__ float4 stage_all[4 * 256];
     __shared__ uint32_t group_count, group_base;
     const int HW = fp.H * fp.W;
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    // Work-groups are dealt to the eight dies round-robin by index.  The groups of one frame are mapped
+    // to one die, so that pixels of neighbouring tiles that show the same triangle find its record in
+    // that die's L2 (frames in whole sets of eight, frames of whole 256-pixel groups; identity otherwise).
+    uint32_t group = blockIdx.x;
+    if (HW % 256 == 0) {
+        const uint32_t per_frame = (uint32_t)HW / 256u, die = group % 8u, turn = group / 8u;
+        if (turn < (B / 8u) * per_frame) group = ((turn / per_frame) * 8u + die) * per_frame + turn % per_frame;
+    }
+    const size_t t = (size_t)group * blockDim.x + threadIdx.x;
     if (blockIdx.x == 0 && threadIdx.x < kShadeQueues) next_count[32 * threadIdx.x] = 0u;
     if (threadIdx.x == 0) group_count = 0u;
     __syncthreads();
