@@ -88,7 +88,10 @@ def test_cluster_culling_never_changes_a_frame():
     _compare(c[0], c[1], ref2, "tilted cameras")
 
 
-def test_random_soup_with_heavy_clipping():
+@pytest.mark.parametrize("threads", [0, 256, 1024])
+def test_random_soup_with_heavy_clipping(threads):
+    """Most triangles straddle a frustum plane: the work-group's clip ring runs full at every group size
+    (its capacity goes with the number of wavefronts)."""
     import oracle
     rng = np.random.default_rng(7)
     n = 3000
@@ -103,9 +106,10 @@ def test_random_soup_with_heavy_clipping():
         Ma = np.stack([synth.view_proj_from_pose((0.1 * k, -0.2, 0.5), 0.4 * k, 0.15 * (k - 3), near=0.05, far=12.0,
                                                  aspect=W / H) for k in range(8)])
         ref = oracle.render_scene(v, idx, Ma, H, W)
-        gd, gi, _ = _render_gpu([scene], [0] * 8, Ma, H, W, background=3.5)
+        gd, gi, info = _render_gpu([scene], [0] * 8, Ma, H, W, background=3.5, threads=threads, splits=1 if threads else 0)
+        assert not threads or info["threads"] == threads
         ref["depth"][ref["tri_id"] == NOHIT] = 3.5
-        _compare(gd, gi, ref, f"soup {H}x{W}")
+        _compare(gd, gi, ref, f"soup {H}x{W} threads {threads}")
 
 
 def test_rgbd_small_scene_matches_oracle_colours():
