@@ -632,45 +632,57 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     const uint32_t* vis_hi = reinterpret_cast<const uint32_t*>(vis) + 1;   // depth word of pixel p is vis_hi[2 p]
 
     // ---- prologue: counters, and the item's blocks ordered near to far
+    const bool sorted = CULL != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)list_cap && nb_item > 1;
     if (tid < 8) counters[tid] = 0u;
     for (int t = tid; t < kHizTiles; t += NT) hiz[t] = 0xFFFFFFFFu;   // nothing drawn yet: no tile hides anything
     for (uint32_t t = tid; t <= ring.mask; t += NT) ring.slot[t] = kClipEmpty;
+    if (sorted)
+        for (int t = tid; t < kDepthBins; t += NT) hist[t] = 0u;
     __syncthreads();
-    const bool sorted = CULL != 0 && nb_item <= kOrderCap && nb_item <= 2u * (uint32_t)list_cap && nb_item > 1;
     if (sorted) {
-        // key: smallest clip w over the block's bounding box (exactly attained at a corner), as a
-        // sortable integer so that any bit pattern, NaN included, has a unique rank
-        uint32_t* keys = reinterpret_cast<uint32_t*>(list);
+        // Counting sort of the blocks in view on the smallest clip w over the block's bounding box
+        // (exactly attained at a corner), in the logarithmic depth bins of the survivor sort: any order
+        // is a correct one, near to far lets occluders come first.  Blocks wholly outside one frustum
+        // plane get no place in the order and are never visited.
+        uint32_t* keys = reinterpret_cast<uint32_t*>(list);     // [nb_item]: bin | place in the bin << 8, or all ones
         for (uint32_t b = tid; b < nb_item; b += NT) {
             const uint32_t gb = b * S + item_split;
-            float wmin = M[15];
-#pragma unroll
-            for (int a = 0; a < 3; ++a) {
-                float lo = g_bbounds[(size_t)a * sc.b_stride + gb], hi = g_bbounds[(size_t)(a + 3) * sc.b_stride + gb];
-                wmin += fminf(M[12 + a] * lo, M[12 + a] * hi);
-            }
-            uint32_t u = __float_as_uint(wmin);
-            uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-            // blocks wholly outside one frustum plane sort last and are never visited
             float lo[3], hi[3];
 #pragma unroll
             for (int a = 0; a < 3; ++a) {
                 lo[a] = g_bbounds[(size_t)a * sc.b_stride + gb];
                 hi[a] = g_bbounds[(size_t)(a + 3) * sc.b_stride + gb];
             }
-            if (box_outside_frustum(M, win, lo[0], lo[1], lo[2], hi[0], hi[1], hi[2])) key = 0xFFFFFFFFu;
-            else atomicAdd(blocks_in_view, 1u);
+            float wmin = M[15];
+#pragma unroll
+            for (int a = 0; a < 3; ++a) wmin += fminf(M[12 + a] * lo[a], M[12 + a] * hi[a]);
+            uint32_t key = 0xFFFFFFFFu;
+            if (!box_outside_frustum(M, win, lo[0], lo[1], lo[2], hi[0], hi[1], hi[2])) {
+                // exponent and top three mantissa bits from 2^-7 upwards; boxes reaching the eye plane first
+                const int k = wmin > 0.0f ? (int)(__float_as_uint(wmin) >> 20) - 120 * 8 : 0;
+                const uint32_t bin = (uint32_t)min(max(k, 0), kDepthBins - 1);
+                key = bin | (atomicAdd(&hist[bin], 1u) << 8);
+            }
             keys[b] = key;
         }
         __syncthreads();
-        for (uint32_t b = tid; b < nb_item; b += NT) {
-            const uint32_t kb = keys[b];
-            uint32_t rank = 0;
-            for (uint32_t o = 0; o < nb_item; ++o) {
-                const uint32_t ko = keys[o];
-                rank += (ko < kb || (ko == kb && o < b)) ? 1u : 0u;
+        if (wave == 0) {   // exclusive prefix sums of the bins: two bins per lane, shuffle scan of the pair sums
+            const uint32_t h0 = hist[2 * lane], h1 = hist[2 * lane + 1];
+            uint32_t incl = h0 + h1;
+#pragma unroll
+            for (int step = 1; step < 64; step <<= 1) {
+                const uint32_t up = (uint32_t)__shfl_up((int)incl, step, 64);
+                if (lane >= step) incl += up;
             }
-            order[rank] = (uint16_t)b;
+            const uint32_t before = incl - (h0 + h1);
+            hist[kDepthBins + 2 * lane] = before;
+            hist[kDepthBins + 2 * lane + 1] = before + h0;
+            if (lane == 63) *blocks_in_view = incl;
+        }
+        __syncthreads();
+        for (uint32_t b = tid; b < nb_item; b += NT) {
+            const uint32_t key = keys[b];
+            if (key != 0xFFFFFFFFu) order[hist[kDepthBins + (key & 0xFFu)] + (key >> 8)] = (uint16_t)b;
         }
     }
     __syncthreads();
