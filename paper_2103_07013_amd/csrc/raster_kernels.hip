@@ -753,20 +753,21 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                         // would make alone when it pops the cluster, at a fortieth of the cost.
                         const bool fine = visible && later_round && bw <= 3 && bh <= 3;
                         if (ballot64(fine) != 0ull) {
-                            const int n = fine ? (bw + 1) * (bh + 1) : 0;
+                            // one footprint row per step: its up to four depth words are read together
                             const uint32_t bound = wb18 << 13;
-                            int at = __mul24(fy, win.w) + fx, col = 0;
-                            bool seen = false;
-                            for (int k = 0; k < 16; ++k) {
-                                const bool act = k < n;
+                            int at = __mul24(fy, win.w) + fx;
+                            uint32_t farthest = 0u;
+                            for (int row = 0; row < 4; ++row) {
+                                const bool act = fine && row <= bh;
                                 if (ballot64(act) == 0ull) break;
-                                const uint32_t dd = act ? vis_hi[2 * at] : 0u;
-                                seen = seen || dd >= bound;
-                                const bool row_end = ++col > bw;
-                                at += row_end ? win.w - bw : 1;
-                                col = row_end ? 0 : col;
+                                const uint32_t d0 = act ? vis_hi[2 * at] : 0u;
+                                const uint32_t d1 = act && bw >= 1 ? vis_hi[2 * (at + 1)] : 0u;
+                                const uint32_t d2 = act && bw >= 2 ? vis_hi[2 * (at + 2)] : 0u;
+                                const uint32_t d3 = act && bw >= 3 ? vis_hi[2 * (at + 3)] : 0u;
+                                farthest = max(farthest, max(max(d0, d1), max(d2, d3)));
+                                at += win.w;
                             }
-                            if (fine && !seen) visible = false;
+                            if (fine && farthest < bound) visible = false;
                         }
                     }
                     st_hiz += (uint32_t)__popcll(ballot64(!visible && foot != kNoPixel));
