@@ -990,14 +990,20 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 }
             }
             // Hi-Z: largest stored depth word per 8x8-pixel tile of the window (empty pixels read as
-            // 0xFFFFFFFF); one wavefront per tile, butterfly maximum
+            // 0xFFFFFFFF); one thread per tile row reads its eight words, eight neighbouring lanes hold the
+            // rows of one tile (a 64x64 window is one pass of the 512 threads)
             const int hty = (win.h + 7) >> 3;
-            for (int t = wave; t < htx * hty; t += NW) {
-                const int px = ((t % htx) << 3) + (lane & 7), py = ((t / htx) << 3) + (lane >> 3);
-                uint32_t dbits = (px < win.w && py < win.h) ? vis_hi[2 * (__mul24(py, win.w) + px)] : 0u;
+            for (int u = tid; u < htx * hty * 8; u += NT) {
+                const int t = u >> 3, py = ((t / htx) << 3) + (u & 7), px0 = (t % htx) << 3;
+                uint32_t dbits = 0u;
+                if (py < win.h) {
+                    const uint32_t* row = vis_hi + 2 * (__mul24(py, win.w) + px0);
 #pragma unroll
-                for (int sh = 32; sh >= 1; sh >>= 1) dbits = max(dbits, (uint32_t)__shfl_xor((int)dbits, sh, 64));
-                if (lane == 0) hiz[t] = dbits;
+                    for (int k = 0; k < 8; ++k) dbits = max(dbits, px0 + k < win.w ? row[2 * k] : 0u);
+                }
+#pragma unroll
+                for (int sh = 4; sh >= 1; sh >>= 1) dbits = max(dbits, (uint32_t)__shfl_xor((int)dbits, sh, 64));
+                if ((u & 7) == 0) hiz[t] = dbits;
             }
             __syncthreads();
             // A block whose box lies behind the largest depth of every tile its footprint touches hides
