@@ -636,8 +636,9 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
     if (tid < 8) counters[tid] = 0u;
     for (int t = tid; t < kHizTiles; t += NT) hiz[t] = 0xFFFFFFFFu;   // nothing drawn yet: no tile hides anything
     for (uint32_t t = tid; t <= ring.mask; t += NT) ring.slot[t] = kClipEmpty;
-    if (sorted)
-        for (int t = tid; t < kDepthBins; t += NT) hist[t] = 0u;
+    // the bin counts of the two counting sorts below: zero whenever no sort is under way (the wavefront
+    // that turns them into offsets clears them again)
+    for (int t = tid; t < kDepthBins; t += NT) hist[t] = 0u;
     __syncthreads();
     if (sorted) {
         // Counting sort of the blocks in view on the smallest clip w over the block's bounding box
@@ -668,6 +669,8 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         __syncthreads();
         if (wave == 0) {   // exclusive prefix sums of the bins: two bins per lane, shuffle scan of the pair sums
             const uint32_t h0 = hist[2 * lane], h1 = hist[2 * lane + 1];
+            hist[2 * lane] = 0u;
+            hist[2 * lane + 1] = 0u;
             uint32_t incl = h0 + h1;
 #pragma unroll
             for (int step = 1; step < 64; step <<= 1) {
@@ -798,14 +801,14 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
         // bins per octave) so that occluders are drawn before what they hide.
         const bool by_depth = occlusion && n_list > 64u;
         if (by_depth) {
-            for (int b = tid; b < 2 * kDepthBins; b += NT) hist[b] = 0u;
-            __syncthreads();
             for (uint32_t i = tid; i < n_list; i += NT)
                 slot_in_bin[i] = (uint16_t)atomicAdd(&hist[depth_bin(list[i])], 1u);
             __syncthreads();
             if (wave == 0) {   // exclusive prefix sums of the bins: two bins per lane, shuffle scan of the pair sums
                 static_assert(kDepthBins == 128, "one wavefront scans two bins per lane");
                 const uint32_t h0 = hist[2 * lane], h1 = hist[2 * lane + 1];
+                hist[2 * lane] = 0u;      // zero again for the next sort
+                hist[2 * lane + 1] = 0u;
                 uint32_t incl = h0 + h1;
 #pragma unroll
                 for (int step = 1; step < 64; step <<= 1) {
