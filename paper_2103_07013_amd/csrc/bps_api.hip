@@ -93,7 +93,7 @@ struct bps_renderer {
     uint8_t* ss_rgb = nullptr;
     int tile_w = 64, tile_h = 64, tiles = 1;
     int list_cap = 2048;
-    int round_target = 2048, first_round = 256;
+    int round_target = 2048, first_round = 192;
     size_t lds = 0;
     size_t max_lds = 0;
     std::string error = "";
