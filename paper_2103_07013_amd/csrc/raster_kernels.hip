@@ -820,8 +820,27 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 hist[kDepthBins + 2 * lane + 1] = before + h0;
             }
             __syncthreads();
-            for (uint32_t i = tid; i < n_list; i += NT)
-                perm[hist[kDepthBins + depth_bin(list[i])] + slot_in_bin[i]] = (uint16_t)i;
+            if (FRAME) {
+                // the instances with a fixed list capacity put the records themselves in order (every thread
+                // carries its few records over a barrier), so that taking a cluster off the list is one read
+                constexpr int kPerThread = ((int)kListCap64 + NT - 1) / NT;
+                u64 rec[kPerThread];
+                uint32_t dst[kPerThread];
+#pragma unroll
+                for (int k = 0; k < kPerThread; ++k) {
+                    const uint32_t i = (uint32_t)tid + (uint32_t)(k * NT);
+                    const bool mine = i < n_list;
+                    rec[k] = mine ? list[i] : 0ull;
+                    dst[k] = mine ? hist[kDepthBins + depth_bin(rec[k])] + slot_in_bin[i] : 0xFFFFFFFFu;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < kPerThread; ++k)
+                    if (dst[k] != 0xFFFFFFFFu) list[dst[k]] = rec[k];
+            } else {
+                for (uint32_t i = tid; i < n_list; i += NT)
+                    perm[hist[kDepthBins + depth_bin(list[i])] + slot_in_bin[i]] = (uint16_t)i;
+            }
             __syncthreads();
             TICK(3);
         }
@@ -837,7 +856,7 @@ __global__ __launch_bounds__(NT, 4) void k_raster(const SceneDev* __restrict__ s
                 if (lane == 0) pop = atomicAdd(pop_count, 1u);
                 pop = __builtin_amdgcn_readfirstlane(pop);
                 if (pop >= n_list) return;
-                const u64 e = list[by_depth ? (uint32_t)perm[pop] : pop];
+                const u64 e = list[(by_depth && !FRAME) ? (uint32_t)perm[pop] : pop];
                 const uint32_t lo32 = __builtin_amdgcn_readfirstlane((uint32_t)e);
                 const uint32_t hi32 = __builtin_amdgcn_readfirstlane((uint32_t)(e >> 32));
                 c_next = lo32 & 0x007FFFFFu;
