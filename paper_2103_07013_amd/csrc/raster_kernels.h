@@ -11,7 +11,7 @@
 //   triangle phase two triangles per lane: outcode reject, bounding box vs pixel centres
 //   compaction     survivors are appended to LDS queues with ballot + prefix count so
 //                  that the expensive steps run on full wavefronts:
-//                    small queue  (per wavefront) triangles touching <= 9 pixel centres, one lane per triangle
+//                    small queue  (per wavefront) triangles touching <= 12 pixel centres, one lane per triangle
 //                    clip ring    (per work-group) triangles straddling a frustum plane, one lane per triangle
 //                  large triangles are rasterised by the whole wavefront, 8x8 pixels at a time.
 // All float arithmetic follows one fixed IEEE sequence (explicit fmaf, no contraction, exact
@@ -62,7 +62,7 @@ struct FrameParams {
 
 constexpr unsigned long long kEmptyKey = ~0ull;
 constexpr int kOrigin = 16384;         // packed screen coordinates are stored relative to pixel 64
-constexpr int kSmallMax = 9;           // pixel centres a "small" triangle may touch (one lane rasterises it)
+constexpr int kSmallMax = 12;          // pixel centres a "small" triangle may touch (one lane rasterises it)
 constexpr uint32_t kInvalid = 0x40u;   // outcode bit: vertex unusable, drop its triangles
 constexpr uint32_t kNoProject = 0x80u; // outcode bit: vertex has no finite screen position (w <= 0 or overflow)
 
