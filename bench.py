@@ -103,6 +103,15 @@ def timed_run(bps, torch, w, flags, steps, warmup, splits, threads, diagnostics=
         ids, vp = cycle[k % len(cycle)]
         bps.bps_render(r.handle, ids, vp, depth, out_rgb=rgb, stream=stream)
 
+    # Before the W warm-up requests the device is brought out of idle: requests are issued for about
+    # 50 ms, so that first-use allocations (the four staging slots, the planning stream) and the ramp of
+    # the device's clocks lie outside the measurement whatever W is (a run with W = 5 came out 1.5 %
+    # slower than one with W = 200 without this).
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < 0.05:
+        for k in range(len(cycle)):
+            submit(k)
+        torch.cuda.synchronize()
     for k in range(max(warmup, len(cycle))):
         submit(k)
     # ---- the headline: K requests, nothing else enqueued, bracketed by synchronisations
